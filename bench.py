@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused attention forward pass (libfa2) on one MI355X.
+
+One "step" is one complete forward pass (one fa2_fwd launch: Q-tile scheduling, K/V staging,
+GEMM-I, online softmax, GEMM-II, epilogue) over one synthetic batch that is already resident in
+HBM.  The headline workload is B=8, H=16, N=2048, d=128, fp16 (the shape the 50%-of-MFMA-peak
+target is stated for); the other four workloads are timed as well and reported under
+"workloads".  FLOPs are those of the two matmuls only, 4*B*H*N^2*d (Section 7 of the paper).
+
+Prints ONE JSON line.  `roofline` prices the kernel against the published dense fp16/bf16 MFMA
+peak of MI355X; `cpu_baseline` is the fp64 CPU oracle timed on this host on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2516.6      # MI355X dense fp16 = bf16 matrix peak (256 CU x 4096 FLOP/clk x 2.4 GHz)
+HBM_PEAK_GBS = 8000.0
+HEADLINE = 3
+
+# HBM bytes per launch of the headline workload measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _device_tensors(index):
+    import torch
+    from paper_2312_11918_amd import workloads
+
+    w, qb, kb, vb = workloads.make_workload(index)
+    tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    q, k, v = (torch.from_numpy(x.view(np.int16)).cuda().view(tdt) for x in (qb, kb, vb))
+    return w, q, k, v
+
+
+def _time_workload(index, steps, warmup):
+    """Times `steps` back-to-back launches with HIP events on the launch stream; returns ms per step."""
+    import torch
+    import paper_2312_11918_amd as fa2
+
+    w, q, k, v = _device_tensors(index)
+    o = torch.empty_like(q)
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    assert bool(torch.isfinite(o).all()), "non-finite output"
+    del q, k, v, o, lse
+    torch.cuda.empty_cache()
+    return w, ev_ms / steps, wall_ms / steps
+
+
+def _cpu_baseline(index, target_seconds=15.0):
+    """The fp64 oracle, as it stands, on this host's cores, on the first batch entries of the workload."""
+    import oracle
+    from paper_2312_11918_amd import workloads
+
+    w, qb, kb, vb = workloads.make_workload(index)
+    # calibration on one head, then as many whole batch entries as fit the time target
+    sl = (slice(0, 1), slice(None), slice(0, 1))
+    q1, k1, v1 = (oracle.widen(x[sl], w.dtype) for x in (qb, kb, vb))
+    t0 = time.perf_counter()
+    oracle.attention(q1, k1, v1, w.scale)
+    t_head = time.perf_counter() - t0
+    nb = int(max(1, min(w.B, target_seconds / max(t_head * w.H, 1e-9))))
+    q, k, v = (oracle.widen(x[:nb], w.dtype) for x in (qb, kb, vb))
+    t0 = time.perf_counter()
+    oracle.attention(q, k, v, w.scale)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * nb * w.H * float(w.N) ** 2 * w.d
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"batch entries 0..{nb - 1} of {w.B} (all {w.H} heads, N={w.N}, d={w.d}) of workload "
+                      f"{w.name}: {flops / 1e9:.1f} GFLOP in {dt:.2f} s, fp64, gcc -O2 + OpenMP"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=HEADLINE, help="headline workload index (1..5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--only-headline", action="store_true", help="do not time the other workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU kernel; run with --gpus 1 "
+              "(no multi-GPU sharding or collectives exist here)", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2312_11918_amd as fa2
+    from paper_2312_11918_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    fa2.load_library()   # fail loudly if the extension is not built
+
+    w, ms, wall_ms = _time_workload(args.workload, args.steps, args.warmup)
+    tflops = w.flops / (ms * 1e-3) / 1e12
+    alg_bytes = 4 * w.B * w.H * w.N * w.d * 2 + 4 * w.B * w.H * w.N
+
+    per_workload = {}
+    if not args.only_headline:
+        for idx in sorted(workloads.CONFIGS):
+            if idx == args.workload:
+                wi, msi = w, ms
+            else:
+                wi0 = workloads.CONFIGS[idx]
+                # about 50 ms of timed launches each
+                est = max(wi0.flops / 0.4e15, 20e-6)
+                si = int(min(max(50e-3 / est, 5), 1000))
+                wi, msi, _ = _time_workload(idx, si, max(3, si // 10))
+            tf = wi.flops / (msi * 1e-3) / 1e12
+            per_workload[wi.name] = {"ms": round(msi, 5), "tflops": round(tf, 2),
+                                     "frac_mfma_peak": round(tf / MFMA_PEAK_TFLOPS, 4),
+                                     "hbm_gbs_algorithmic": round((4 * wi.B * wi.H * wi.N * wi.d * 2 + 4 * wi.B * wi.H * wi.N) / (msi * 1e-3) / 1e9, 1)}
+
+    out = {
+        "metric": "attention fwd TFLOP/s (4*B*H*N^2*d)",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "wall_ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp16" if w.dtype == "fp16" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": False,
+                   "scale": "1/sqrt(d)", "inputs": "i.i.d. N(0,1), seeded, resident in HBM"},
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "algorithmic_flops_per_launch": w.flops, "algorithmic_hbm_bytes_per_launch": alg_bytes,
+                     "kernel": "fa2_fwd_kernel", "kernel_ms": round(ms, 5)},
+        "workloads": per_workload,
+        "paper_context": "H100 PCIe, fp16: 295.7 TFLOP/s best at d=128 (Table 1), 39% of its 756 TFLOP/s peak; not a target",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline(args.workload)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,79 @@
+/*
+ * libfa2 -- fused scaled dot-product attention forward pass for AMD MI355X (gfx950 / CDNA4).
+ *
+ * The operation is the one stated in Section 2 of "A Case Study in CUDA Kernel Fusion:
+ * Implementing FlashAttention-2 on NVIDIA Hopper Architecture using the CUTLASS Library"
+ * (arXiv 2312.11918):
+ *
+ *      O = softmax(scale * Q K^T) V        independently for every batch entry and head,
+ *
+ * computed as in its Algorithm 2 (FlashAttention-2 forward): for each tile of query rows the
+ * kernel streams tiles of K and V, forms S = Q K^T on the matrix cores, keeps a running row
+ * maximum and row sum (online softmax), accumulates O = P V on the matrix cores and divides by
+ * the row sum at the end.  S and P live in registers only and never reach device memory.
+ *
+ * Besides O the library returns the row-wise log-sum-exp of the scaled logits,
+ *      LSE[b,h,i] = ln sum_j exp(scale * q_i . k_j),
+ * which Algorithm 2 holds implicitly as (rowmax, rowsum) and which callers need to merge
+ * attention computed over disjoint key ranges.
+ *
+ * Plain C ABI: pointers and sizes only.  Every data pointer is a DEVICE pointer owned by the caller.
+ */
+#ifndef FA2_H_
+#define FA2_H_
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of Q, K, V and O. */
+enum { FA2_FP16 = 0, /* IEEE binary16 */
+       FA2_BF16 = 1  /* bfloat16      */ };
+
+/* Return codes. */
+enum {
+  FA2_OK = 0,
+  FA2_ERR_INVALID_ARG = -1, /* NULL Q/K/V/O; B, H, N or d <= 0; scale not finite or <= 0;
+                               a pointer not 16-byte aligned (LSE: 4-byte)            */
+  FA2_ERR_UNSUPPORTED = -2, /* d not in {64, 128}; N not a multiple of 128; unknown dtype;
+                               a problem too large for 32-bit tile counts             */
+  FA2_ERR_LAUNCH = -3       /* the HIP runtime refused the launch                     */
+};
+
+/*
+ * fa2_fwd -- attention forward pass (Section 2 formula, Algorithm 2 schedule), non-causal,
+ * no mask, no dropout, self-attention shape (as many keys as queries).
+ *
+ *  Q, K, V  in   device, [B][N][H][d] contiguous, element (b,n,h,k) at ((b*N+n)*H+h)*d+k
+ *                (the paper's (batch, seqlen, heads, headdim) order), 16-bit elements of `dtype`.
+ *  O        out  device, same shape, layout and element type as Q.  Rounded once, from the fp32
+ *                accumulator, to nearest-even.
+ *  LSE      out  device, [B][H][N] contiguous fp32, natural logarithm; may be NULL (not written).
+ *  B,H,N,d       batch, heads, sequence length, head dimension.  d must be 64 or 128 and N a
+ *                multiple of 128.
+ *  scale         multiplies Q K^T before the softmax; callers pass 1/sqrt(d).  Must be finite
+ *                and > 0 (the kernel takes the row maximum before scaling).
+ *  dtype         FA2_FP16 or FA2_BF16.  Products are accumulated in fp32; P is rounded to `dtype`
+ *                (nearest-even) before the second matrix product, the row sum is taken in fp32
+ *                from the unrounded P.
+ *  stream        a hipStream_t passed as void*; NULL is the default stream.
+ *
+ * The call only enqueues one kernel on `stream` and returns; it allocates nothing, keeps no state
+ * and never synchronises.  Buffers must stay valid until the stream has run the kernel.  O and LSE
+ * must not overlap Q, K or V.  On any error nothing is launched and the outputs are untouched.
+ * Inputs holding NaN or infinities give unspecified outputs.  Safe to call from several threads.
+ * The launch uses the device that is current on the calling thread; all pointers must belong to it.
+ */
+int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
+            float scale, int dtype, void* stream);
+
+/* Static, NUL-terminated description of a return code (never NULL). */
+const char* fa2_strerror(int code);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fa2_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FA2_H_ */

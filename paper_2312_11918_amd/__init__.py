@@ -1,0 +1,11 @@
+"""FlashAttention-2 forward pass for MI355X (gfx950): a hand-written HIP kernel behind a C ABI.
+
+``fa2_fwd`` and friends are thin ctypes marshalling over ``libfa2.so``; every step of the
+attention path runs in the HIP kernel.  The shared library is loaded on first use and a
+missing library is an error (there is no CPU fallback).
+"""
+from .binding import (FA2_BF16, FA2_FP16, FA2_OK, FA2_ERR_INVALID_ARG, FA2_ERR_LAUNCH, FA2_ERR_UNSUPPORTED,
+                      Fa2Error, fa2_fwd, fa2_fwd_raw, fa2_strerror, fa2_version, library_path, load_library)
+
+__all__ = ["FA2_BF16", "FA2_FP16", "FA2_OK", "FA2_ERR_INVALID_ARG", "FA2_ERR_LAUNCH", "FA2_ERR_UNSUPPORTED",
+           "Fa2Error", "fa2_fwd", "fa2_fwd_raw", "fa2_strerror", "fa2_version", "library_path", "load_library"]

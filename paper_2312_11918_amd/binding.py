@@ -1,0 +1,107 @@
+"""ctypes binding of libfa2's C ABI (see include/fa2.h).  Argument marshalling only.
+
+``fa2_fwd_raw`` takes raw device addresses; ``fa2_fwd`` takes torch CUDA tensors, which are used
+purely as owners of device memory (``data_ptr()``) and of the current HIP stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+FA2_FP16 = 0
+FA2_BF16 = 1
+FA2_OK = 0
+FA2_ERR_INVALID_ARG = -1
+FA2_ERR_UNSUPPORTED = -2
+FA2_ERR_LAUNCH = -3
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libfa2.so")
+_lib = None
+
+
+class Fa2Error(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"fa2 error {code}: {message}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libfa2.so (built in-tree by ``build.build_library``).  A missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is not built; run `python -m paper_2312_11918_amd.build` "
+                "(there is no fallback path)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.fa2_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, vp]
+        lib.fa2_fwd.restype = ci
+        lib.fa2_strerror.argtypes = [ci]
+        lib.fa2_strerror.restype = ctypes.c_char_p
+        lib.fa2_version.argtypes = []
+        lib.fa2_version.restype = ci
+        _lib = lib
+    return _lib
+
+
+def fa2_strerror(code: int) -> str:
+    return load_library().fa2_strerror(int(code)).decode()
+
+
+def fa2_version() -> int:
+    return int(load_library().fa2_version())
+
+
+def fa2_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, N, d, scale, dtype, stream=None) -> int:
+    """Call ``fa2_fwd`` with raw device addresses (ints or None); returns the C return code."""
+    return int(load_library().fa2_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, int(B), int(H), int(N), int(d),
+                                      float(scale), int(dtype), stream))
+
+
+def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, stream=None):
+    """Attention forward on torch CUDA tensors ``[B, N, H, d]`` (fp16 or bf16, contiguous).
+
+    Returns ``(O, LSE)`` with O like ``q`` and LSE ``[B, H, N]`` fp32 (``None`` if ``return_lse`` is
+    false).  The kernel is enqueued on ``stream`` (a ``torch.cuda.Stream``) or on torch's current stream.
+    """
+    import torch
+
+    if not (q.is_cuda and k.is_cuda and v.is_cuda):
+        raise ValueError("q, k, v must be CUDA tensors (there is no CPU path)")
+    if q.dtype == torch.float16:
+        dtype = FA2_FP16
+    elif q.dtype == torch.bfloat16:
+        dtype = FA2_BF16
+    else:
+        raise ValueError(f"unsupported element type {q.dtype}")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share one element type")
+    if q.dim() != 4 or k.shape != q.shape or v.shape != q.shape:
+        raise ValueError(f"q, k, v must all be [B, N, H, d]; got {tuple(q.shape)}, {tuple(k.shape)}, {tuple(v.shape)}")
+    if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
+        raise ValueError("q, k, v must be contiguous")
+    B, N, H, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
+        raise ValueError("out must match q in shape, dtype, device and be contiguous")
+    if return_lse:
+        if lse is None:
+            lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+        elif tuple(lse.shape) != (B, H, N) or lse.dtype != torch.float32 or not lse.is_contiguous():
+            raise ValueError("lse must be a contiguous fp32 [B, H, N] tensor")
+    else:
+        lse = None
+    with torch.cuda.device(q.device):
+        s = stream if stream is not None else torch.cuda.current_stream()
+        rc = fa2_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                         None if lse is None else lse.data_ptr(), B, H, N, d, scale, dtype, s.cuda_stream)
+    if rc != FA2_OK:
+        raise Fa2Error(rc, fa2_strerror(rc))
+    return out, lse

@@ -1,0 +1,73 @@
+"""Host-side behaviour of the C ABI that needs no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2312_11918_amd as fa2
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "fa2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fa2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    assert {"fa2_fwd", "fa2_strerror", "fa2_version"} <= set(_declared_functions())
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(fa2.library_path())
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in include/fa2.h but not exported"
+
+
+def test_version_and_strerror():
+    assert fa2.fa2_version() >= 100
+    for code in (fa2.FA2_OK, fa2.FA2_ERR_INVALID_ARG, fa2.FA2_ERR_UNSUPPORTED, fa2.FA2_ERR_LAUNCH, 12345):
+        assert isinstance(fa2.fa2_strerror(code), str) and fa2.fa2_strerror(code)
+
+
+P = 0x1000  # a 16-byte aligned, never dereferenced "device address": validation must reject first
+
+
+@pytest.mark.parametrize("args,code", [
+    (dict(q=None), fa2.FA2_ERR_INVALID_ARG),
+    (dict(k=None), fa2.FA2_ERR_INVALID_ARG),
+    (dict(v=None), fa2.FA2_ERR_INVALID_ARG),
+    (dict(o=None), fa2.FA2_ERR_INVALID_ARG),
+    (dict(B=0), fa2.FA2_ERR_INVALID_ARG),
+    (dict(H=-1), fa2.FA2_ERR_INVALID_ARG),
+    (dict(N=0), fa2.FA2_ERR_INVALID_ARG),
+    (dict(d=0), fa2.FA2_ERR_INVALID_ARG),
+    (dict(scale=0.0), fa2.FA2_ERR_INVALID_ARG),
+    (dict(scale=-0.125), fa2.FA2_ERR_INVALID_ARG),
+    (dict(scale=float("nan")), fa2.FA2_ERR_INVALID_ARG),
+    (dict(scale=float("inf")), fa2.FA2_ERR_INVALID_ARG),
+    (dict(q=P + 8), fa2.FA2_ERR_INVALID_ARG),
+    (dict(o=P + 2), fa2.FA2_ERR_INVALID_ARG),
+    (dict(lse=P + 2), fa2.FA2_ERR_INVALID_ARG),
+    (dict(d=96), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(d=256), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(N=100), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(N=64), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(dtype=7), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(B=1 << 20, N=1 << 20), fa2.FA2_ERR_UNSUPPORTED),
+])
+def test_bad_arguments_are_rejected_without_a_launch(args, code):
+    a = dict(q=P, k=P, v=P, o=P, lse=P, B=1, H=2, N=256, d=64, scale=0.125, dtype=fa2.FA2_FP16)
+    a.update(args)
+    rc = fa2.fa2_fwd_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["N"], a["d"], a["scale"], a["dtype"])
+    assert rc == code
+
+
+def test_torch_wrapper_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 128, 1, 64, dtype=torch.float16)
+    with pytest.raises(ValueError):
+        fa2.fa2_fwd(x, x, x, 0.125)
