@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--workload", type=int, default=HEADLINE, help="headline workload index (1..5)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--only-headline", action="store_true", help="do not time the other workloads")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="K",
+                    help="first run K plain device copies of the headline Q tensor (a kernel of known HBM "
+                         "traffic, for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel; run with --gpus 1 "
@@ -115,6 +118,16 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
     fa2.load_library()   # fail loudly if the extension is not built
+
+    if args.copy_calibration > 0:
+        wc, qc, _, _ = _device_tensors(args.workload)
+        dst = torch.empty_like(qc)
+        for _ in range(args.copy_calibration):
+            dst.copy_(qc)
+        torch.cuda.synchronize()
+        print(f"copy calibration: {args.copy_calibration} copies of {qc.numel() * 2} bytes "
+              f"(reads {qc.numel() * 2} B, writes {qc.numel() * 2} B each)", file=sys.stderr)
+        del qc, dst
 
     w, ms, wall_ms = _time_workload(args.workload, args.steps, args.warmup)
     tflops = w.flops / (ms * 1e-3) / 1e12

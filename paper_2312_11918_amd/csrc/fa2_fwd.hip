@@ -39,6 +39,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kBr = 32 * kWaves;     // query rows per workgroup (32 per wavefront)
 constexpr int kBc = 64;              // keys per K/V tile
 constexpr int kXcds = 8;             // accelerator complex dies; workgroup i is dispatched to XCD i % 8
+constexpr float kLazyLog2 = 8.0f;    // the rowmax reference moves only when exceeded by 2^8
 
 // Element-type specifics: the MFMA flavour and the fp32 -> 16-bit pack (round to nearest even).
 template <int DT> struct Elem;
@@ -82,16 +83,24 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t* p) {
   return __builtin_bit_cast(u32x2, v);
 }
 
-// Row strides of the LDS tiles in 16-bit elements.  K is read with 16-byte loads, lane = key row:
-// a stride of (row bytes + 16) spreads 16 consecutive rows over all banks.  V is read with the
-// transpose load, 8 key rows x 64 bytes per instruction: a stride of 64 bytes modulo 256 puts
-// four consecutive rows side by side across the 64 banks.
-template <int D> struct Lds {
-  static constexpr int kKStride = D + 8;
-  static constexpr int kVStride = D + 32;
-  static constexpr int kKTile = kBc * kKStride;
-  static constexpr int kVTile = kBc * kVStride;
+// LDS tile geometry.  A K or V tile is kBc rows of D 16-bit elements, stored row-major WITHOUT
+// padding (the direct global->LDS loads write 1 KiB of consecutive LDS per wavefront instruction),
+// with the 16-byte chunks of every row permuted by an XOR so that the operand reads are free of
+// bank conflicts (the role of the paper's 128-byte shared-memory swizzle, Section 3.2):
+//   K is read with 16-byte loads, lane = key row: 16 consecutive rows must land in 16 different
+//     16-byte slots of the 256-byte bank period            -> chunk ^= f(row) over the whole period;
+//   V is read with the transpose load, 4 key rows x 32 bytes per group of 16 lanes: the 4 rows must
+//     land in different 64-byte quarters of the bank period -> chunk ^= g(row) << 2.
+template <int D> struct Tile {
+  static constexpr int kChunksPerRow = D / 8;                      // 16-byte chunks per row
+  static constexpr int kElems = kBc * D;                           // elements per tile
+  static constexpr int kLoadsPerWave = kElems * 2 / 1024 / kWaves; // 1 KiB wavefront loads per tile and wave
+  static __device__ __forceinline__ int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+  static __device__ __forceinline__ int swz_v(int row) { return (D == 128 ? (row & 3) : ((row >> 1) & 1)) << 2; }
 };
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
 
 template <int DT, int D>
 __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __restrict__ Q,
@@ -101,18 +110,25 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
                                                               int H, int N, float scale_log2e, int n_qtiles,
                                                               int total_tiles) {
   using E = Elem<DT>;
-  using L = Lds<D>;
+  using T = Tile<D>;
   constexpr int kKSteps = D / 16;   // MFMA steps along d for S^T = K Q^T
   constexpr int kDBlocks = D / 32;  // 32-row blocks of O^T
-  constexpr int kChunksPerRow = D / 8;                        // 16-byte chunks per K/V row
-  constexpr int kChunksPerThread = kBc * kChunksPerRow / kThreads;
+  constexpr int kKBlocks = kBc / 32;  // 32-key blocks of S^T
+  constexpr int kTSteps = kBc / 16;   // MFMA steps along the keys for O^T = V^T P^T
+  constexpr int kSteps1 = kKBlocks * kKSteps;  // MFMAs of GEMM-I per tile
+  constexpr int kSteps2 = kTSteps * kDBlocks;  // MFMAs of GEMM-II per tile
+  constexpr int kRing = 4;                     // operand fragments in flight between LDS and the MFMAs
 
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][L::kKTile];
-  __shared__ __attribute__((aligned(16))) uint16_t v_lds[2][L::kVTile];
+  // Two buffers each for K and V.  They are separate objects on purpose: the compiler then knows that a
+  // load in flight into one buffer cannot alias the operand reads from the other.
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds0[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds1[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds0[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds1[T::kElems];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform, kept in a scalar register
   const int r = lane & 31;   // column of the 32x32 MFMA tile owned by this lane = query within the wave
   const int hh = lane >> 5;  // which half of the wavefront
 
@@ -133,6 +149,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
 
   const size_t row_stride = (size_t)H * D;                          // elements between consecutive tokens
   const size_t head_base = ((size_t)b * N * H + (size_t)h) * D;     // element (b, 0, h, 0)
+  const size_t tile_stride = (size_t)kBc * row_stride;              // elements between consecutive K/V tiles
   const int q_row = qt * kBr + wave * 32 + r;
 
   // Q_i fragment, held in registers for the whole loop: B operand of S^T = K Q^T.
@@ -143,91 +160,139 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
     for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
   }
 
-  // Staging of one K/V tile: thread t moves 16-byte chunks t, t+256, ... of the tile.
-  u32x4 kreg[kChunksPerThread], vreg[kChunksPerThread];
-  auto load_tile = [&](int j) {
-    const size_t tile_base = head_base + (size_t)j * kBc * row_stride;
+  // Direct global->LDS staging.  Wavefront w issues loads number w*kLoadsPerWave + i of a tile; load n
+  // fills LDS bytes [1024 n, 1024 n + 1024) of the tile, lane l the 16-byte chunk 64 n + l.  The chunk's
+  // row and (swizzled) position decide which global chunk the lane fetches.
+  uint32_t k_src[T::kLoadsPerWave], v_src[T::kLoadsPerWave];  // byte offsets inside a tile, per lane
 #pragma unroll
-    for (int i = 0; i < kChunksPerThread; ++i) {
-      const int c = tid + i * kThreads;
-      const int row = c / kChunksPerRow, col = c % kChunksPerRow;
-      const size_t off = tile_base + (size_t)row * row_stride + col * 8;
-      kreg[i] = *reinterpret_cast<const u32x4*>(K + off);
-      vreg[i] = *reinterpret_cast<const u32x4*>(V + off);
-    }
-  };
-  auto store_tile = [&](int buf) {
+  for (int i = 0; i < T::kLoadsPerWave; ++i) {
+    const int chunk = 64 * (wave * T::kLoadsPerWave + i) + lane;
+    const int row = chunk / T::kChunksPerRow, pos = chunk % T::kChunksPerRow;
+    k_src[i] = (uint32_t)row * (uint32_t)(row_stride * 2) + 16u * (uint32_t)(pos ^ T::swz_k(row));
+    v_src[i] = (uint32_t)row * (uint32_t)(row_stride * 2) + 16u * (uint32_t)(pos ^ T::swz_v(row));
+  }
+  const uint16_t* k_head = K + head_base;
+  const uint16_t* v_head = V + head_base;
+  // src_tile is wavefront-uniform (scalar base), the per-lane part is a 32-bit byte offset.
+  auto stage = [&](const uint16_t* src_tile, const uint32_t (&src)[T::kLoadsPerWave], uint16_t* lds_tile) {
+    const char* base = reinterpret_cast<const char*>(src_tile);
+    asm volatile("" : "+s"(base));  // keep the scalar base apart from the per-lane offsets
 #pragma unroll
-    for (int i = 0; i < kChunksPerThread; ++i) {
-      const int c = tid + i * kThreads;
-      const int row = c / kChunksPerRow, col = c % kChunksPerRow;
-      *reinterpret_cast<u32x4*>(&k_lds[buf][row * L::kKStride + col * 8]) = kreg[i];
-      *reinterpret_cast<u32x4*>(&v_lds[buf][row * L::kVStride + col * 8]) = vreg[i];
+    for (int i = 0; i < T::kLoadsPerWave; ++i) {
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(base + src[i]),
+                                       (lds_void_ptr)(lds_tile + 512 * (wave * T::kLoadsPerWave + i)), 16, 0, 0);
     }
   };
 
-  // Accumulators of Algorithm 2: O^T (fp32), running rowmax (kept unscaled, and scaled by
-  // scale*log2(e) as the reference point of the exponentials) and running rowsum.  Each half of the
-  // wavefront keeps the partial rowsum of its own keys; the two are added in the epilogue.
+  // Per-lane LDS element offsets of the operand reads (row part + swizzled chunk part).
+  int k_addr[kKSteps];  // K fragment of MFMA step ks: row r (+32 per key block), chunk 2 ks + hh
+#pragma unroll
+  for (int ks = 0; ks < kKSteps; ++ks) k_addr[ks] = r * D + 8 * ((2 * ks + hh) ^ T::swz_k(r));
+  int v_addr[kDBlocks];  // V fragment of d-block db: row 4 hh + (lane%16)/4 (+16 per step, +8 for the upper half)
+  {
+    const int l16 = lane & 15;
+    const int row0 = 4 * hh + (l16 >> 2);
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db) {
+      const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((l16 & 3) >> 1);
+      v_addr[db] = row0 * D + 8 * (chunk ^ T::swz_v(row0)) + 4 * (l16 & 1);
+    }
+  }
+
+  // Accumulators of Algorithm 2: O^T (fp32), the rowmax reference and the running rowsum.  Each half
+  // of the wavefront keeps the partial rowsum of its own keys; the two are added in the epilogue.
   f32x16 ot[kDBlocks];
 #pragma unroll
   for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
     for (int v = 0; v < 16; ++v) ot[db][v] = 0.f;
-  float m_run = -INFINITY;   // running rowmax of the unscaled logits q.k
-  float mc_run = -INFINITY;  // the same times scale*log2(e)
+  f32x16 st[kKBlocks];       // S^T of the tile being processed
+  float m_ref = -INFINITY;   // reference point of the exponentials, in units of the unscaled logits q.k
+  float mc_ref = -INFINITY;  // m_ref * scale * log2(e)
   float l_run = 0.f;
 
-  const int n_tiles = N / kBc;
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
+  // Operand fragment of MFMA step `step` of GEMM-I (K rows) / GEMM-II (V columns, transposed by the load).
+  auto k_frag = [&](const uint16_t* kt, int step) -> u32x4 {
+    const int ks = step / kKBlocks, kb = step % kKBlocks;
+    return *reinterpret_cast<const u32x4*>(kt + k_addr[ks] + kb * 32 * D);
+  };
+  auto v_frag = [&](const uint16_t* vt, int step) -> u32x4 {
+    const int t = step / kDBlocks, db = step % kDBlocks;
+    const uint16_t* p = vt + v_addr[db] + t * 16 * D;
+    const u32x2 lo = lds_read_tr16(p);
+    const u32x2 hi = lds_read_tr16(p + 8 * D);
+    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+  };
 
-  // Per-lane LDS element offsets of the operand reads.
-  const int k_off = r * L::kKStride + 8 * hh;
-  const int v_off = (4 * hh + ((lane & 15) >> 2)) * L::kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-  for (int j = 0; j < n_tiles; ++j) {
-    const int buf = j & 1;
-    if (j + 1 < n_tiles) load_tile(j + 1);  // in flight during this tile's MFMAs
-
-    // GEMM-I (transposed): S^T[key][query] for 2 blocks of 32 keys.
-    f32x16 st[kBc / 32];
+  // GEMM-I (transposed): S^T[key][query] = K_j Q_i^T, fragments prefetched kRing steps ahead.
+  auto gemm1 = [&](const uint16_t* kt) {
+    u32x4 ring[kRing];
 #pragma unroll
-    for (int kb = 0; kb < kBc / 32; ++kb) {
+    for (int i = 0; i < kRing; ++i) ring[i] = k_frag(kt, i);
+#pragma unroll
+    for (int kb = 0; kb < kKBlocks; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) st[kb][v] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < kKSteps; ++ks) {
-        const u32x4 kf = *reinterpret_cast<const u32x4*>(&k_lds[buf][k_off + kb * 32 * L::kKStride + ks * 16]);
-        st[kb] = E::mfma(kf, qf[ks], st[kb]);
-      }
+    for (int i = 0; i < kSteps1; ++i) {
+      const int ks = i / kKBlocks, kb = i % kKBlocks;
+      st[kb] = E::mfma(ring[i % kRing], qf[ks], st[kb]);
+      if (i + kRing < kSteps1) ring[i % kRing] = k_frag(kt, i + kRing);
+      __builtin_amdgcn_sched_barrier(0);
     }
+  };
 
-    // Online softmax for this lane's query.  The maximum is taken on the unscaled logits (valid for
-    // scale > 0) and the scale is folded into the exponent: exp(scale*(s-m)) = exp2(s*c - m*c).
+  // One iteration of Algorithm 2's inner loop, software-pipelined by one tile on the K side: softmax of
+  // S_j, O += P~_j V_j, then S_{j+1} = K_{j+1} Q^T.  Every iteration thus has one block of softmax
+  // arithmetic and one block of back-to-back MFMAs, which the two wavefronts sharing a SIMD overlap.
+  auto iteration = [&](int j, int n_tiles, const uint16_t* v_cur, const uint16_t* k_next, uint16_t* v_fill,
+                       uint16_t* k_fill) {
+    // Copy/GEMM overlap (Section 6): V_{j+1} and K_{j+2} fly into the idle buffers during this iteration.
+    if (j + 1 < n_tiles) stage(v_head + (size_t)(j + 1) * tile_stride, v_src, v_fill);
+    if (j + 2 < n_tiles) stage(k_head + (size_t)(j + 2) * tile_stride, k_src, k_fill);
+
+    // ---- online softmax for this lane's query (Algorithm 2: rowmax, P~, rowsum, rescale) ----
+    // The maximum is taken on the unscaled logits (valid for scale > 0) and the scale is folded into
+    // the exponent: exp(scale*(s - m)) = exp2(s*c - m*c) with c = scale*log2(e).
+    __builtin_amdgcn_s_setprio(0);
     float mx = st[0][0];
 #pragma unroll
-    for (int kb = 0; kb < kBc / 32; ++kb)
+    for (int kb = 0; kb < kKBlocks; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[kb][v]);
     mx = max_with_partner_half(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float mc_new = m_new * scale_log2e;
-    const float alpha = __builtin_amdgcn_exp2f(mc_run - mc_new);  // exp(m_old - m_new); 0 on the first tile
-    m_run = m_new;
-    mc_run = mc_new;
-
-    float rowsum = 0.f;
-    u32x4 pf[kBc / 16];
+    // The reference point only has to keep the exponentials in range, it need not be the exact
+    // running maximum: it is moved (and O, l rescaled by exp(m_old - m_new)) only when the tile maximum
+    // exceeds it by more than 2^kLazyLog2; until then P~ <= 2^kLazyLog2.  The result is unchanged
+    // because the reference cancels in O / l; on the first tile m_ref = -inf forces the move.
+    const bool move = (mx - m_ref) * scale_log2e > kLazyLog2;
+    if (__builtin_amdgcn_ballot_w64(move) != 0) {
+      const float m_new = move ? mx : m_ref;
+      const float mc_new = m_new * scale_log2e;
+      const float alpha = __builtin_amdgcn_exp2f(mc_ref - mc_new);  // exp(m_old - m_new); 0 on the first tile
+      m_ref = m_new;
+      mc_ref = mc_new;
+      l_run *= alpha;
 #pragma unroll
-    for (int kb = 0; kb < kBc / 32; ++kb) {
+      for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
+    }
+
+    // first V fragments: independent of P~, so their LDS latency hides behind the exponentials
+    u32x4 ring[kRing];
+#pragma unroll
+    for (int i = 0; i < kRing; ++i) ring[i] = v_frag(v_cur, i);
+
+    float rowsum[4] = {0.f, 0.f, 0.f, 0.f};
+    u32x4 pf[kTSteps];
+#pragma unroll
+    for (int kb = 0; kb < kKBlocks; ++kb) {
       float p[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][v], scale_log2e, -mc_new));
-        rowsum += p[v];
-      }
+      for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][v], scale_log2e, -mc_ref));
+#pragma unroll
+      for (int v = 0; v < 16; ++v) rowsum[v & 3] += p[v];
       // P~ rounded to 16 bit: registers 8t..8t+7 of a 32-key block are the 8 B-operand slots of MFMA step t.
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -235,29 +300,43 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
                                E::pack2(p[8 * t + 4], p[8 * t + 5]), E::pack2(p[8 * t + 6], p[8 * t + 7])};
       }
     }
-    l_run = alpha * l_run + rowsum;
-#pragma unroll
-    for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
+    l_run += (rowsum[0] + rowsum[1]) + (rowsum[2] + rowsum[3]);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // GEMM-II (transposed): O^T[d][query] += V^T P^T.  Slot i of lane-half hh in step t is key
+    // ---- GEMM-II (transposed): O^T[d][query] += V_j^T P~^T.  Slot i of lane-half hh in step t is key
     // 16t + 8(i/4) + 4hh + i%4, the key of accumulator register 8t+i of GEMM-I.
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int t = 0; t < kBc / 16; ++t) {
-#pragma unroll
-      for (int db = 0; db < kDBlocks; ++db) {
-        const uint16_t* vp = &v_lds[buf][v_off + t * 16 * L::kVStride + db * 32];
-        const u32x2 lo = lds_read_tr16(vp);
-        const u32x2 hi = lds_read_tr16(vp + 8 * L::kVStride);
-        ot[db] = E::mfma(u32x4{lo[0], lo[1], hi[0], hi[1]}, pf[t], ot[db]);
-      }
+    for (int i = 0; i < kSteps2; ++i) {
+      const int t = i / kDBlocks, db = i % kDBlocks;
+      ot[db] = E::mfma(ring[i % kRing], pf[t], ot[db]);
+      if (i + kRing < kSteps2) ring[i % kRing] = v_frag(v_cur, i + kRing);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // ---- GEMM-I of the next tile
+    if (j + 1 < n_tiles) gemm1(k_next);
 
-    // The other buffer was last read during tile j-1; every wavefront has passed the barrier that
-    // ended that iteration, so it can be overwritten now.
-    if (j + 1 < n_tiles) store_tile(buf ^ 1);
+    // Publish the staged tiles: every load of this wavefront has landed, then all wavefronts meet.  The
+    // barrier also guarantees that nobody still reads the buffers that the next iteration refills.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
+  };
+
+  const int n_tiles = N / kBc;
+  stage(k_head, k_src, k_lds0);
+  stage(v_head, v_src, v_lds0);
+  if (n_tiles > 1) stage(k_head + tile_stride, k_src, k_lds1);
+  // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
+#pragma unroll
+  for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  __syncthreads();
+  gemm1(k_lds0);
+
+  // LDS at the top of iteration j: V_j in v_lds[j&1], K_{j+1} in k_lds[(j+1)&1].
+  for (int j = 0; j < n_tiles; j += 2) {
+    iteration(j, n_tiles, v_lds0, k_lds1, v_lds1, k_lds0);
+    if (j + 1 < n_tiles) iteration(j + 1, n_tiles, v_lds1, k_lds0, v_lds0, k_lds1);
   }
 
   // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
@@ -275,7 +354,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
     }
   }
   if (LSE != nullptr && hh == 0) {
-    LSE[((size_t)b * H + h) * N + q_row] = mc_run * 0.69314718055994530942f + __builtin_logf(l_tot);
+    LSE[((size_t)b * H + h) * N + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
   }
 }
 
