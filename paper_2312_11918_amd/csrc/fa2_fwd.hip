@@ -100,7 +100,7 @@ template <int D> struct Tile {
 };
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef __attribute__((address_space(1))) const void* global_void_ptr;
+constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gfx9-family: 32-bit data format, no swizzle
 
 template <int DT, int D>
 __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __restrict__ Q,
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
     for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
   }
 
-  // Direct global->LDS staging.  Wavefront w issues loads number w*kLoadsPerWave + i of a tile; load n
+  // Direct global->LDS staging (buffer_load ... lds).  Wavefront w issues loads number w*kLoadsPerWave + i of a tile; load n
   // fills LDS bytes [1024 n, 1024 n + 1024) of the tile, lane l the 16-byte chunk 64 n + l.  The chunk's
   // row and (swizzled) position decide which global chunk the lane fetches.
   uint32_t k_src[T::kLoadsPerWave], v_src[T::kLoadsPerWave];  // byte offsets inside a tile, per lane
@@ -171,16 +171,20 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
     k_src[i] = (uint32_t)row * (uint32_t)(row_stride * 2) + 16u * (uint32_t)(pos ^ T::swz_k(row));
     v_src[i] = (uint32_t)row * (uint32_t)(row_stride * 2) + 16u * (uint32_t)(pos ^ T::swz_v(row));
   }
-  const uint16_t* k_head = K + head_base;
-  const uint16_t* v_head = V + head_base;
-  // src_tile is wavefront-uniform (scalar base), the per-lane part is a 32-bit byte offset.
-  auto stage = [&](const uint16_t* src_tile, const uint32_t (&src)[T::kLoadsPerWave], uint16_t* lds_tile) {
-    const char* base = reinterpret_cast<const char*>(src_tile);
-    asm volatile("" : "+s"(base));  // keep the scalar base apart from the per-lane offsets
+  // Buffer descriptors (base, byte range) of this head's K and V rows: a raw buffer load takes a scalar
+  // descriptor, a scalar tile offset and the 32-bit per-lane offset, and its range check turns any
+  // offset past the last row into zeros instead of a fault.
+  const uint32_t head_bytes = (uint32_t)(((size_t)(N - 1) * row_stride + D) * 2);
+  const __amdgpu_buffer_rsrc_t k_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(K + head_base), 0, (int)head_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(V + head_base), 0, (int)head_bytes, kBufferFlags);
+  const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
+  auto stage = [&](__amdgpu_buffer_rsrc_t rsrc, int j, const uint32_t (&src)[T::kLoadsPerWave], uint16_t* lds_tile) {
 #pragma unroll
     for (int i = 0; i < T::kLoadsPerWave; ++i) {
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(base + src[i]),
-                                       (lds_void_ptr)(lds_tile + 512 * (wave * T::kLoadsPerWave + i)), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(lds_tile + 512 * (wave * T::kLoadsPerWave + i)), 16,
+                                               (int)src[i], (int)((uint32_t)j * tile_bytes), 0, 0);
     }
   };
 
@@ -248,8 +252,8 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
   auto iteration = [&](int j, int n_tiles, const uint16_t* v_cur, const uint16_t* k_next, uint16_t* v_fill,
                        uint16_t* k_fill) {
     // Copy/GEMM overlap (Section 6): V_{j+1} and K_{j+2} fly into the idle buffers during this iteration.
-    if (j + 1 < n_tiles) stage(v_head + (size_t)(j + 1) * tile_stride, v_src, v_fill);
-    if (j + 2 < n_tiles) stage(k_head + (size_t)(j + 2) * tile_stride, k_src, k_fill);
+    if (j + 1 < n_tiles) stage(v_rsrc, j + 1, v_src, v_fill);
+    if (j + 2 < n_tiles) stage(k_rsrc, j + 2, k_src, k_fill);
 
     // ---- online softmax for this lane's query (Algorithm 2: rowmax, P~, rowsum, rescale) ----
     // The maximum is taken on the unscaled logits (valid for scale > 0) and the scale is folded into
@@ -323,9 +327,9 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
   };
 
   const int n_tiles = N / kBc;
-  stage(k_head, k_src, k_lds0);
-  stage(v_head, v_src, v_lds0);
-  if (n_tiles > 1) stage(k_head + tile_stride, k_src, k_lds1);
+  stage(k_rsrc, 0, k_src, k_lds0);
+  stage(v_rsrc, 0, v_src, v_lds0);
+  if (n_tiles > 1) stage(k_rsrc, 1, k_src, k_lds1);
   // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
 #pragma unroll
   for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
@@ -389,6 +393,8 @@ extern "C" int fa2_fwd(const void* Q, const void* K, const void* V, void* O, flo
   if (N % kBr != 0) return FA2_ERR_UNSUPPORTED;
   // element offsets are computed in 64 bits; the row index b*N+n must still fit the tile arithmetic
   if ((long long)B * N > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
+  // the K/V rows of one batch entry are addressed with 32-bit byte offsets from a buffer descriptor
+  if ((unsigned long long)N * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32)) return FA2_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
     return d == 64 ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, s)
