@@ -67,6 +67,24 @@ enum {
 int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
             float scale, int dtype, void* stream);
 
+/* Tile shapes (the counterpart of the paper's QBLK x KBLK choice, Section 7 and Table 1). */
+enum {
+  FA2_VARIANT_AUTO = 0,   /* pick by problem shape (what fa2_fwd does)                                  */
+  FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (32 per wavefront), 2 workgroups per CU       */
+  FA2_VARIANT_WIDE = 2    /* 256 query rows per workgroup (64 per wavefront), 1 workgroup per CU;
+                             needs N to be a multiple of 256                                            */
+};
+
+/*
+ * fa2_fwd_variant -- fa2_fwd with an explicit tile shape, for tile-shape sweeps in the manner of the
+ * paper's Table 1.  Arguments, layout, ownership and error behaviour are those of fa2_fwd; `variant`
+ * is one of FA2_VARIANT_*.  An unknown variant is FA2_ERR_INVALID_ARG, a variant that cannot run the
+ * shape is FA2_ERR_UNSUPPORTED.  All variants compute the same function; results may differ in the
+ * last bits because the summation order differs.
+ */
+int fa2_fwd_variant(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
+                    float scale, int dtype, int variant, void* stream);
+
 /* Static, NUL-terminated description of a return code (never NULL). */
 const char* fa2_strerror(int code);
 

@@ -14,6 +14,9 @@ FA2_OK = 0
 FA2_ERR_INVALID_ARG = -1
 FA2_ERR_UNSUPPORTED = -2
 FA2_ERR_LAUNCH = -3
+FA2_VARIANT_AUTO = 0
+FA2_VARIANT_NARROW = 1
+FA2_VARIANT_WIDE = 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libfa2.so")
@@ -42,6 +45,8 @@ def load_library():
         vp, ci = ctypes.c_void_p, ctypes.c_int
         lib.fa2_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, vp]
         lib.fa2_fwd.restype = ci
+        lib.fa2_fwd_variant.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, ci, vp]
+        lib.fa2_fwd_variant.restype = ci
         lib.fa2_strerror.argtypes = [ci]
         lib.fa2_strerror.restype = ctypes.c_char_p
         lib.fa2_version.argtypes = []
@@ -64,11 +69,19 @@ def fa2_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, N, d, scale, dtype, s
                                       float(scale), int(dtype), stream))
 
 
-def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, stream=None):
+def fa2_fwd_variant_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, N, d, scale, dtype, variant, stream=None) -> int:
+    """Call ``fa2_fwd_variant`` (explicit tile shape) with raw device addresses; returns the C return code."""
+    return int(load_library().fa2_fwd_variant(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, int(B), int(H), int(N), int(d),
+                                              float(scale), int(dtype), int(variant), stream))
+
+
+def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, stream=None,
+            variant: int = FA2_VARIANT_AUTO):
     """Attention forward on torch CUDA tensors ``[B, N, H, d]`` (fp16 or bf16, contiguous).
 
     Returns ``(O, LSE)`` with O like ``q`` and LSE ``[B, H, N]`` fp32 (``None`` if ``return_lse`` is
     false).  The kernel is enqueued on ``stream`` (a ``torch.cuda.Stream``) or on torch's current stream.
+    ``variant`` selects the tile shape (``FA2_VARIANT_*``); the default lets the library choose.
     """
     import torch
 
@@ -100,8 +113,9 @@ def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, 
         lse = None
     with torch.cuda.device(q.device):
         s = stream if stream is not None else torch.cuda.current_stream()
-        rc = fa2_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                         None if lse is None else lse.data_ptr(), B, H, N, d, scale, dtype, s.cuda_stream)
+        rc = fa2_fwd_variant_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                 None if lse is None else lse.data_ptr(), B, H, N, d, scale, dtype, variant,
+                                 s.cuda_stream)
     if rc != FA2_OK:
         raise Fa2Error(rc, fa2_strerror(rc))
     return out, lse

@@ -21,6 +21,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "fa2.h"
 
 namespace {
@@ -42,6 +45,16 @@ constexpr int kXcds = 8;             // accelerator complex dies; workgroup i is
 constexpr float kLazyLog2 = 8.0f;    // the rowmax reference moves only when exceeded by 2^8
 
 // Element-type specifics: the MFMA flavour and the fp32 -> 16-bit pack (round to nearest even).
+// Compile-time loop: calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
 template <int DT> struct Elem;
 template <> struct Elem<FA2_FP16> {
   static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
@@ -362,17 +375,378 @@ __global__ __launch_bounds__(kThreads, 2) void fa2_fwd_kernel(const uint16_t* __
   }
 }
 
+// -------------------------------------------------------------------------------------------------
+// Wide kernel: 64 query rows per wavefront, one workgroup (4 wavefronts, 256 rows) per CU.
+//
+// With 32 rows per wavefront every MFMA needs a fresh 1 KiB operand fragment from LDS, which at the
+// full MFMA rate is exactly the LDS bandwidth of a CU (128 B/clk): that design tops out on LDS.  Here a
+// fragment of K or V feeds two MFMAs (query halves A and B), which halves the LDS traffic per FLOP.  The
+// price is registers (O^T alone is 128 per lane at d=128), so only one wavefront fits a SIMD and the
+// overlap of softmax arithmetic with the matrix cores has to happen inside the instruction stream of
+// that one wavefront: the loop is software-pipelined over STAGES of 32 keys,
+//     stage s:   matrix cores:  S_{s+1} = K_{s+1} Q^T   and   O += P~_{s-1} V_{s-1}
+//                vector ALU:    online softmax of S_s -> P~_s
+// and the softmax is cut into small chunks that are placed between the MFMAs in program order, so
+// they issue in the shadow of the 8-pass MFMAs.  (The paper's Section 6 overlaps copies with the two
+// GEMMs and leaves the softmax exposed; its register-pressure discussion in Section 7 is the same
+// trade-off that fixes the tile shape here.)
+constexpr int kWideBr = 64 * kWaves;  // query rows per workgroup of the wide kernel
+constexpr int kStageKeys = 32;        // keys per pipeline stage (half a K/V tile)
+constexpr int kWideMinTiles = 256;    // automatic selection: at least one 256-row tile per CU
+
+template <int DT, int D>
+__global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_t* __restrict__ Q,
+                                                                   const uint16_t* __restrict__ K,
+                                                                   const uint16_t* __restrict__ V,
+                                                                   uint16_t* __restrict__ O, float* __restrict__ LSE,
+                                                                   int H, int N, float scale_log2e, int n_qtiles,
+                                                                   int total_tiles) {
+  using E = Elem<DT>;
+  using T = Tile<D>;
+  constexpr int kKSteps = D / 16;                // K fragments per stage (MFMA steps along d)
+  constexpr int kDBlocks = D / 32;               // 32-row blocks of O^T
+  constexpr int kVFrags = 2 * kDBlocks;          // V fragments per stage (2 key steps x d blocks)
+  constexpr int kFrags = kKSteps + kVFrags;      // operand fragments per stage, each feeds 2 MFMAs
+  constexpr int kSlots = 2 * kFrags;             // MFMAs per stage
+  constexpr int kRing = 4;                       // fragments in flight between LDS and the MFMAs
+  // softmax chunk schedule over the MFMA slots of a stage
+  constexpr int kMaxChunks = kSlots / 8;         // slots that hold the 16 v_max3 of the rowmax
+  constexpr int kMaxPerChunk = 8 / kMaxChunks;   // v_max3 per half and chunk
+  constexpr int kExpFirst = kMaxChunks + 2;      // first slot of the exponentials
+  constexpr int kExpChunks = kSlots - kExpFirst;
+
+  // Four buffers each for K and V tiles (128 KiB at d=128): global loads are issued three tiles ahead,
+  // far enough to cover an HBM miss.  Separate objects, so that the compiler can tell a load in flight
+  // into one buffer from the operand reads of another.
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds0[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds1[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds2[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds3[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds0[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds1[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds2[T::kElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds3[T::kElems];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31;
+  const int hh = lane >> 5;
+
+  int tile;
+  {
+    const int wg = blockIdx.x;
+    const int per = total_tiles / kXcds, rem = total_tiles % kXcds;
+    const int xcd = wg % kXcds, idx = wg / kXcds;
+    tile = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int bh = tile / n_qtiles;
+  const int qt = tile - bh * n_qtiles;
+  const int b = bh / H;
+  const int h = bh - b * H;
+
+  const size_t row_stride = (size_t)H * D;
+  const size_t head_base = ((size_t)b * N * H + (size_t)h) * D;
+  const size_t tile_stride = (size_t)kBc * row_stride;
+  const int q_row0 = qt * kWideBr + wave * 64 + r;  // half A; half B is 32 rows further
+
+  // Q fragments of both halves (B operands of S^T = K Q^T), resident for the whole loop.
+  u32x4 qf[2][kKSteps];
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const uint16_t* qp = Q + head_base + (size_t)(q_row0 + 32 * half) * row_stride + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) qf[half][ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+  }
+
+  // Direct global->LDS staging, as in the narrow kernel.
+  uint32_t k_src[T::kLoadsPerWave], v_src[T::kLoadsPerWave];
+#pragma unroll
+  for (int i = 0; i < T::kLoadsPerWave; ++i) {
+    const int chunk = 64 * (wave * T::kLoadsPerWave + i) + lane;
+    const int row = chunk / T::kChunksPerRow, pos = chunk % T::kChunksPerRow;
+    k_src[i] = (uint32_t)row * (uint32_t)(row_stride * 2) + 16u * (uint32_t)(pos ^ T::swz_k(row));
+    v_src[i] = (uint32_t)row * (uint32_t)(row_stride * 2) + 16u * (uint32_t)(pos ^ T::swz_v(row));
+  }
+  const uint32_t head_bytes = (uint32_t)(((size_t)(N - 1) * row_stride + D) * 2);
+  const __amdgpu_buffer_rsrc_t k_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(K + head_base), 0, (int)head_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(V + head_base), 0, (int)head_bytes, kBufferFlags);
+  const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
+  auto stage_in = [&](__amdgpu_buffer_rsrc_t rsrc, int j, const uint32_t (&src)[T::kLoadsPerWave],
+                      uint16_t* lds_tile) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < T::kLoadsPerWave; ++i) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(lds_tile + 512 * (wave * T::kLoadsPerWave + i)), 16,
+                                               (int)src[i], (int)((uint32_t)j * tile_bytes), 0, 0);
+    }
+  };
+
+  // Per-lane LDS element offsets of the operand reads inside a 32-key block.
+  int k_addr[kKSteps];
+#pragma unroll
+  for (int ks = 0; ks < kKSteps; ++ks) k_addr[ks] = r * D + 8 * ((2 * ks + hh) ^ T::swz_k(r));
+  int v_addr[kDBlocks];
+  {
+    const int l16 = lane & 15;
+    const int row0 = 4 * hh + (l16 >> 2);
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db) {
+      const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((l16 & 3) >> 1);
+      v_addr[db] = row0 * D + 8 * (chunk ^ T::swz_v(row0)) + 4 * (l16 & 1);
+    }
+  }
+  // Fragment f of a stage: f < kKSteps is the K fragment of MFMA step f, otherwise the V fragment of
+  // key step t and d-block db with f - kKSteps = t * kDBlocks + db.
+  auto frag = [&](const uint16_t* k_blk, const uint16_t* v_blk, int f) __attribute__((always_inline)) -> u32x4 {
+    if (f < kKSteps) return *reinterpret_cast<const u32x4*>(k_blk + k_addr[f]);
+    const int g = f - kKSteps, t = g / kDBlocks, db = g % kDBlocks;
+    const uint16_t* p = v_blk + v_addr[db] + t * 16 * D;
+    const u32x2 lo = lds_read_tr16(p);
+    const u32x2 hi = lds_read_tr16(p + 8 * D);
+    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+  };
+
+  // State of Algorithm 2 for the two query halves.
+  f32x16 ot[2][kDBlocks];
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) ot[half][db][v] = 0.f;
+  f32x16 st[2][2];      // [pipeline slot][half]: S^T of a 32-key stage
+  u32x4 pf[2][2][2];    // [pipeline slot][half][key step]: P~ rounded to 16 bit, B operands of GEMM-II
+  float m_ref[2] = {-INFINITY, -INFINITY};
+  float mc_ref[2] = {-INFINITY, -INFINITY};
+  float l_run[2] = {0.f, 0.f};
+  float alpha_pend[2] = {1.f, 1.f};  // rescale of O decided by the previous stage's softmax, not yet applied
+  bool rescale_pend = false;
+
+  // One pipeline stage.  kG1: compute S of the next stage from k_blk into st[kSlot ^ 1];
+  // kSm: softmax of st[kSlot] into pf[kSlot]; kG2: O += P~ V with pf[kSlot ^ 1] and v_blk.
+  auto stage = [&](auto g1_tag, auto sm_tag, auto g2_tag, auto slot_tag, const uint16_t* k_blk,
+                   const uint16_t* v_blk) __attribute__((always_inline)) {
+    constexpr bool kG1 = decltype(g1_tag)::value, kSm = decltype(sm_tag)::value, kG2 = decltype(g2_tag)::value;
+    constexpr int kSlot = decltype(slot_tag)::value;
+    constexpr int kFirst = kG1 ? 0 : kKSteps;          // first and one-past-last fragment of this stage
+    constexpr int kLast = kG2 ? kFrags : kKSteps;
+
+    if (kG2 && rescale_pend) {  // rare: the reference point moved in the previous stage
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) ot[half][db][v] *= alpha_pend[half];
+    }
+
+    u32x4 ring[kRing];
+#pragma unroll
+    for (int i = 0; i < kRing; ++i)
+      if (kFirst + i < kLast) ring[i] = frag(k_blk, v_blk, kFirst + i);
+
+    float mx[2], rs[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, pe[2] = {0.f, 0.f};
+    // softmax work of MFMA slot m.  Every chunk ends by handing its results to an empty asm statement:
+    // that keeps the optimiser from sinking the arithmetic out of its slot (its results are only
+    // consumed in the next stage).
+    auto softmax_chunk = [&](auto m_tag) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_tag)::value;
+      if constexpr (m < kMaxChunks) {
+        static_for<2>([&](auto half_tag) {
+          constexpr int half = decltype(half_tag)::value;
+          static_for<kMaxPerChunk>([&](auto i_tag) {
+            constexpr int v = 2 * (m * kMaxPerChunk + decltype(i_tag)::value);
+            if constexpr (v == 0) mx[half] = fmaxf(st[kSlot][half][0], st[kSlot][half][1]);
+            else mx[half] = fmaxf(fmaxf(mx[half], st[kSlot][half][v]), st[kSlot][half][v + 1]);
+          });
+          asm volatile("" : "+v"(mx[half]));
+        });
+      } else if constexpr (m == kMaxChunks) {
+        static_for<2>([&](auto half_tag) {
+          constexpr int half = decltype(half_tag)::value;
+          mx[half] = max_with_partner_half(mx[half]);
+          asm volatile("" : "+v"(mx[half]));
+        });
+      } else if constexpr (m == kMaxChunks + 1) {
+        // lazy reference point, see the narrow kernel: move only when exceeded by 2^kLazyLog2
+        bool move[2];
+        static_for<2>([&](auto half_tag) {
+          constexpr int half = decltype(half_tag)::value;
+          move[half] = (mx[half] - m_ref[half]) * scale_log2e > kLazyLog2;
+          const float m_new = move[half] ? mx[half] : m_ref[half];
+          const float mc_new = m_new * scale_log2e;
+          alpha_pend[half] = __builtin_amdgcn_exp2f(mc_ref[half] - mc_new);
+          m_ref[half] = m_new;
+          mc_ref[half] = mc_new;
+          l_run[half] *= alpha_pend[half];
+          asm volatile("" : "+v"(alpha_pend[half]), "+v"(mc_ref[half]), "+v"(l_run[half]));
+        });
+        rescale_pend = __builtin_amdgcn_ballot_w64(move[0] || move[1]) != 0;
+      } else if constexpr (m < kSlots) {
+        constexpr int c = m - kExpFirst;
+        static_for<32>([&](auto e_tag) {
+          constexpr int e = decltype(e_tag)::value;
+          if constexpr (e * kExpChunks / 32 == c) {
+            constexpr int half = (e >> 1) & 1, v = 2 * (e >> 2) + (e & 1);
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kSlot][half][v], scale_log2e, -mc_ref[half]));
+            rs[half][e & 1] += p;
+            asm volatile("" : "+v"(rs[half][e & 1]));
+            if constexpr ((e & 1) == 0) {
+              pe[half] = p;
+            } else {
+              uint32_t packed = E::pack2(pe[half], p);
+              asm volatile("" : "+v"(packed));
+              pf[kSlot][half][v / 8][(v % 8) / 2] = packed;
+            }
+          }
+        });
+      }
+    };
+
+    static_for<2 * (kLast - kFirst)>([&](auto i_tag) {
+      constexpr int i = decltype(i_tag)::value;  // slot of this stage
+      constexpr int f = kFirst + i / 2, half = i % 2;
+      const u32x4 a = ring[(f - kFirst) % kRing];
+      if constexpr (f < kKSteps) {
+        if constexpr (f == 0) {
+          f32x16 zero;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+          st[kSlot ^ 1][half] = E::mfma(a, qf[half][f], zero);
+        } else {
+          st[kSlot ^ 1][half] = E::mfma(a, qf[half][f], st[kSlot ^ 1][half]);
+        }
+      } else {
+        constexpr int g = f - kKSteps, t = g / kDBlocks, db = g % kDBlocks;
+        ot[half][db] = E::mfma(a, pf[kSlot ^ 1][half][t], ot[half][db]);
+      }
+      if constexpr (half == 1 && f + kRing < kLast) ring[(f - kFirst) % kRing] = frag(k_blk, v_blk, f + kRing);
+      if constexpr (kSm) softmax_chunk(i_tag);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if constexpr (kSm) {
+      // stages without GEMM-I or GEMM-II have fewer slots than chunks: run the rest back to back
+      static_for<kSlots - 2 * (kLast - kFirst)>([&](auto i_tag) {
+        softmax_chunk(std::integral_constant<int, decltype(i_tag)::value + 2 * (kLast - kFirst)>{});
+      });
+#pragma unroll
+      for (int half = 0; half < 2; ++half) l_run[half] += rs[half][0] + rs[half][1];
+    }
+  };
+
+  using std::false_type;
+  using std::true_type;
+  using slot0 = std::integral_constant<int, 0>;
+  using slot1 = std::integral_constant<int, 1>;
+
+  // Pipeline over stages s = 0 .. n_stages (inclusive): stage s runs softmax(s), GEMM-I(s+1), GEMM-II(s-1).
+  // K tile t (blocks 2t, 2t+1) sits in k_lds[t % 4], V tile t in v_lds[t % 4].  Tile step j is the pair
+  // of stages 2j+1, 2j+2: it reads K tile j+1 and V tile j and ends with the one barrier per tile.  After
+  // that barrier K tile j+1 and V tile j are dead and their buffers are refilled with K tile j+5 and
+  // V tile j+4.  The loads needed by step j+1 (K tile j+2, V tile j+1) were issued three barriers
+  // earlier; each barrier issues 2*kLoadsPerWave loads per wavefront, so waiting until at most
+  // 2*(2*kLoadsPerWave) are outstanding is enough while every barrier issues its full set.
+  constexpr int kLoadsPerBarrier = 2 * T::kLoadsPerWave;
+  constexpr int kRelaxedVmcnt = 2 * kLoadsPerBarrier;
+  static_assert(kRelaxedVmcnt < 64, "vmcnt is a 6-bit counter");
+  // s_waitcnt immediate with expcnt and lgkmcnt left at their maximum (no wait)
+  constexpr int kWaitRelaxed = (kRelaxedVmcnt & 15) | ((kRelaxedVmcnt >> 4) << 14) | 0x0F70;
+  constexpr int kWaitAll = 0x0F70;  // vmcnt(0)
+
+  const int n_tiles = N / kBc;  // a multiple of 4 because N is a multiple of 256
+  stage_in(k_rsrc, 0, k_src, k_lds0);
+  stage_in(v_rsrc, 0, v_src, v_lds0);
+  stage_in(k_rsrc, 1, k_src, k_lds1);
+  stage_in(v_rsrc, 1, v_src, v_lds1);
+  stage_in(k_rsrc, 2, k_src, k_lds2);
+  stage_in(v_rsrc, 2, v_src, v_lds2);
+  stage_in(k_rsrc, 3, k_src, k_lds3);
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[half][ks]));
+  __builtin_amdgcn_s_waitcnt(kWaitAll);
+  __syncthreads();
+
+  // prologue: GEMM-I(0) alone, then stage 0 (no GEMM-II yet)
+  stage(true_type{}, false_type{}, false_type{}, slot1{}, k_lds0, v_lds0);                 // writes st[0]
+  stage(true_type{}, true_type{}, false_type{}, slot0{}, k_lds0 + kStageKeys * D, v_lds0);  // softmax(0), S_1 -> st[1]
+  __syncthreads();  // everyone is done with K tile 0
+  if (4 < n_tiles) stage_in(k_rsrc, 4, k_src, k_lds0);
+  stage_in(v_rsrc, 3, v_src, v_lds3);
+
+  auto tile_step = [&](auto relaxed_tag, int j, const uint16_t* k_next, const uint16_t* v_cur, uint16_t* k_fill,
+                       uint16_t* v_fill) __attribute__((always_inline)) {
+    // stage 2j+1: softmax(2j+1), S_{2j+2} from K tile j+1 first half, O += P~_{2j} V (V tile j first half)
+    stage(true_type{}, true_type{}, true_type{}, slot1{}, k_next, v_cur);
+    // stage 2j+2: softmax(2j+2), S_{2j+3} from K tile j+1 second half, O += P~_{2j+1} V (V tile j second half)
+    stage(true_type{}, true_type{}, true_type{}, slot0{}, k_next + kStageKeys * D, v_cur + kStageKeys * D);
+    // this wavefront's parts of K tile j+2 and V tile j+1 have landed ...
+    if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
+    else __builtin_amdgcn_s_waitcnt(kWaitAll);
+    __syncthreads();  // ... and everybody's; and nobody reads K tile j+1 / V tile j any more
+    if (j + 5 < n_tiles) stage_in(k_rsrc, j + 5, k_src, k_fill);
+    if (j + 4 < n_tiles) stage_in(v_rsrc, j + 4, v_src, v_fill);
+  };
+  int j = 0;
+  for (; j + 8 <= n_tiles; j += 4) {  // every barrier of these steps issues its full set of loads
+    tile_step(true_type{}, j, k_lds1, v_lds0, k_lds1, v_lds0);
+    tile_step(true_type{}, j + 1, k_lds2, v_lds1, k_lds2, v_lds1);
+    tile_step(true_type{}, j + 2, k_lds3, v_lds2, k_lds3, v_lds2);
+    tile_step(true_type{}, j + 3, k_lds0, v_lds3, k_lds0, v_lds3);
+  }
+  // tail: j = n_tiles - 4; three more full steps, then the two draining stages
+  tile_step(false_type{}, j, k_lds1, v_lds0, k_lds1, v_lds0);
+  tile_step(false_type{}, j + 1, k_lds2, v_lds1, k_lds2, v_lds1);
+  tile_step(false_type{}, j + 2, k_lds3, v_lds2, k_lds3, v_lds2);
+  // last softmax stage (S of the last 32 keys was produced by the stage before): no GEMM-I
+  stage(false_type{}, true_type{}, true_type{}, slot1{}, k_lds0, v_lds3);
+  // draining stage: only O += P~_{last} V
+  stage(false_type{}, false_type{}, true_type{}, slot0{}, k_lds0, v_lds3 + kStageKeys * D);
+
+  // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum).
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const float l_tot = sum_with_partner_half(l_run[half]);
+    const float inv_l = 1.0f / l_tot;
+    const int q_row = q_row0 + 32 * half;
+    uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w = {E::pack2(ot[half][db][4 * g + 0] * inv_l, ot[half][db][4 * g + 1] * inv_l),
+                   E::pack2(ot[half][db][4 * g + 2] * inv_l, ot[half][db][4 * g + 3] * inv_l)};
+        *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
+      }
+    }
+    if (LSE != nullptr && hh == 0) {
+      LSE[((size_t)b * H + h) * N + q_row] = mc_ref[half] * 0.69314718055994530942f + __builtin_logf(l_tot);
+    }
+  }
+}
+
 template <int DT, int D>
 int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, float scale,
-           hipStream_t stream) {
-  const int n_qtiles = N / kBr;
+           int variant, hipStream_t stream) {
+  const float scale_log2e = scale * 1.44269504088896340736f;
+  const bool wide = variant == FA2_VARIANT_WIDE;
+  const int n_qtiles = N / (wide ? kWideBr : kBr);
   const long long total = (long long)B * H * n_qtiles;
   if (total > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
-  const float scale_log2e = scale * 1.44269504088896340736f;
-  hipLaunchKernelGGL((fa2_fwd_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                     static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                     static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e, n_qtiles,
-                     (int)total);
+  if (wide) {
+    hipLaunchKernelGGL((fa2_fwd_wide_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
+                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
+                       n_qtiles, (int)total);
+  } else {
+    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
+                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
+                       n_qtiles, (int)total);
+  }
   return hipGetLastError() == hipSuccess ? FA2_OK : FA2_ERR_LAUNCH;
 }
 
@@ -380,28 +754,41 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 
 }  // namespace
 
-extern "C" int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
-                       float scale, int dtype, void* stream) {
+extern "C" int fa2_fwd_variant(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N,
+                               int d, float scale, int dtype, int variant, void* stream) {
   // All validation happens before the first HIP call: an error launches nothing.
   if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return FA2_ERR_INVALID_ARG;
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return FA2_ERR_INVALID_ARG;
   if (!(scale > 0.0f) || !(scale <= 3.0e38f)) return FA2_ERR_INVALID_ARG;  // rejects NaN, inf, <= 0
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(LSE, 4))
     return FA2_ERR_INVALID_ARG;
+  if (variant != FA2_VARIANT_AUTO && variant != FA2_VARIANT_NARROW && variant != FA2_VARIANT_WIDE)
+    return FA2_ERR_INVALID_ARG;
   if (dtype != FA2_FP16 && dtype != FA2_BF16) return FA2_ERR_UNSUPPORTED;
   if (d != 64 && d != 128) return FA2_ERR_UNSUPPORTED;
   if (N % kBr != 0) return FA2_ERR_UNSUPPORTED;
+  if (variant == FA2_VARIANT_WIDE && N % kWideBr != 0) return FA2_ERR_UNSUPPORTED;
   // element offsets are computed in 64 bits; the row index b*N+n must still fit the tile arithmetic
   if ((long long)B * N > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
   // the K/V rows of one batch entry are addressed with 32-bit byte offsets from a buffer descriptor
   if ((unsigned long long)N * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32)) return FA2_ERR_UNSUPPORTED;
+  if (variant == FA2_VARIANT_AUTO) {
+    // The wide kernel needs N to be a multiple of its 256-row tile and enough tiles to give every CU one.
+    const long long wide_tiles = (long long)B * H * (N / kWideBr);
+    variant = (N % kWideBr == 0 && wide_tiles >= kWideMinTiles) ? FA2_VARIANT_WIDE : FA2_VARIANT_NARROW;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
-    return d == 64 ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, s)
-                   : launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, s);
+    return d == 64 ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, s)
+                   : launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, s);
   }
-  return d == 64 ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, s)
-                 : launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, s);
+  return d == 64 ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, s)
+                 : launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, s);
+}
+
+extern "C" int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
+                       float scale, int dtype, void* stream) {
+  return fa2_fwd_variant(Q, K, V, O, LSE, B, H, N, d, scale, dtype, FA2_VARIANT_AUTO, stream);
 }
 
 extern "C" const char* fa2_strerror(int code) {

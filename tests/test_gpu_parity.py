@@ -26,13 +26,13 @@ def _to_device(bits, dtype):
     return t.view(torch.float16 if dtype == "fp16" else torch.bfloat16)
 
 
-def _run_gpu(qb, kb, vb, dtype, scale):
+def _run_gpu(qb, kb, vb, dtype, scale, variant=0):
     """Runs fa2_fwd and returns (O as fp64 numpy [B,N,H,d], LSE as fp64 numpy [B,H,N])."""
     torch = _torch()
     q, k, v = (_to_device(x, dtype) for x in (qb, kb, vb))
     o = torch.full_like(q, float("nan"))
     lse = torch.full((q.shape[0], q.shape[2], q.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
-    fa2.fa2_fwd(q, k, v, scale, out=o, lse=lse)
+    fa2.fa2_fwd(q, k, v, scale, out=o, lse=lse, variant=variant)
     torch.cuda.synchronize()
     return o.double().cpu().numpy(), lse.double().cpu().numpy()
 
@@ -66,6 +66,26 @@ def test_parity_elementwise(B, H, N, d, dtype):
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
     o, lse = _run_gpu(qb, kb, vb, dtype, scale)
     _check(o, lse, o_ref, lse_ref, f"B{B} H{H} N{N} d{d} {dtype}")
+
+
+@pytest.mark.parametrize("variant", [fa2.FA2_VARIANT_NARROW, fa2.FA2_VARIANT_WIDE])
+@pytest.mark.parametrize("B,H,N,d,dtype", [
+    (1, 2, 256, 64, "fp16"),      # one wide tile, 4 key tiles: prologue + tail only
+    (2, 3, 512, 128, "fp16"),     # 2 wide tiles per head, one main-loop trip
+    (1, 2, 1024, 128, "bf16"),    # several main-loop trips
+    (1, 5, 768, 64, "bf16"),      # 15 wide tiles: not a multiple of the 8 XCDs; n_tiles = 12
+    (1, 1, 1280, 128, "fp16"),    # n_tiles = 20
+])
+def test_parity_explicit_variants(B, H, N, d, dtype, variant):
+    seed = 2000 + 3 * N + d + B
+    print(f"variant {variant} case B={B} H={H} N={N} d={d} {dtype} seed={seed}", flush=True)
+    # large-logit keys only for fp16: a bf16 output of magnitude >= 2.56 cannot meet 1e-2 by rounding alone
+    frac = 0.01 if dtype == "fp16" else 0.0
+    qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, seed, k_outlier_frac=frac, k_outlier_gain=6.0)
+    scale = float(np.float32(d) ** np.float32(-0.5))
+    o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
+    o, lse = _run_gpu(qb, kb, vb, dtype, scale, variant)
+    _check(o, lse, o_ref, lse_ref, f"variant {variant} B{B} H{H} N{N} d{d} {dtype}")
 
 
 def test_parity_workload_1_full():
