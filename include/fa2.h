@@ -71,8 +71,10 @@ int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, in
 enum {
   FA2_VARIANT_AUTO = 0,   /* pick by problem shape (what fa2_fwd does)                                  */
   FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (32 per wavefront), 2 workgroups per CU       */
-  FA2_VARIANT_WIDE = 2    /* 256 query rows per workgroup (64 per wavefront), 1 workgroup per CU;
+  FA2_VARIANT_WIDE = 2,   /* 256 query rows per workgroup (4 wavefronts x 64 rows), 1 workgroup per CU;
                              needs N to be a multiple of 256                                            */
+  FA2_VARIANT_NARROW8 = 3 /* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
+                             K/V loaded three tiles ahead; needs N to be a multiple of 256              */
 };
 
 /*

@@ -17,6 +17,7 @@ FA2_ERR_LAUNCH = -3
 FA2_VARIANT_AUTO = 0
 FA2_VARIANT_NARROW = 1
 FA2_VARIANT_WIDE = 2
+FA2_VARIANT_NARROW8 = 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libfa2.so")
