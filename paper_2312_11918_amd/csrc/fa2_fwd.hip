@@ -355,17 +355,34 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- GEMM-II (transposed): O^T[d][query] += V_j^T P~^T.  Slot i of lane-half hh in step t is key
-    // 16t + 8(i/4) + 4hh + i%4, the key of accumulator register 8t+i of GEMM-I.
+    // 16t + 8(i/4) + 4hh + i%4, the key of accumulator register 8t+i of GEMM-I.  GEMM-I of the next tile
+    // follows in the same stream of MFMA steps, so its first K fragments are fetched under the last MFMAs of
+    // GEMM-II and no LDS latency is exposed between the two products.
     __builtin_amdgcn_s_setprio(1);
+    constexpr bool kNext = decltype(next_tag)::value;
+    constexpr int kStepsAll = kSteps2 + (kNext ? kSteps1 : 0);
+    auto any_frag = [&](int step) __attribute__((always_inline)) -> u32x4 {
+      return step < kSteps2 ? v_frag(v_cur, step) : k_frag(k_next, step - kSteps2);
+    };
 #pragma unroll
-    for (int i = 0; i < kSteps2; ++i) {
-      const int t = i / kDBlocks, db = i % kDBlocks;
-      ot[db] = E::mfma(ring[i % kRing], pf[t], ot[db]);
-      if (i + kRing < kSteps2) ring[i % kRing] = v_frag(v_cur, i + kRing);
+    for (int i = 0; i < kStepsAll; ++i) {
+      if (i < kSteps2) {
+        const int t = i / kDBlocks, db = i % kDBlocks;
+        ot[db] = E::mfma(ring[i % kRing], pf[t], ot[db]);
+      } else {
+        const int i1 = i - kSteps2, ks = i1 / kKBlocks, kb = i1 % kKBlocks;
+        if (ks == 0) {
+          f32x16 zero;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+          st[kb] = E::mfma(ring[i % kRing], qf[ks], zero);
+        } else {
+          st[kb] = E::mfma(ring[i % kRing], qf[ks], st[kb]);
+        }
+      }
+      if (i + kRing < kStepsAll) ring[i % kRing] = any_frag(i + kRing);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // ---- GEMM-I of the next tile
-    if constexpr (decltype(next_tag)::value) gemm1(k_next);
   };
 
   // LDS schedule.  K tile t lives in k_lds[t % kNBuf], V tile t in v_lds[t % kNBuf].  Iteration j reads
