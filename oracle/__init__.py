@@ -42,6 +42,10 @@ def _load():
         lib.fa_oracle_forward.restype = ci
         lib.fa_oracle_rows.argtypes = [dp, dp, dp, ip, ci, dp, dp, ci, ci, ci, ci, ci, cd]
         lib.fa_oracle_rows.restype = ci
+        lib.fa_oracle_forward_masked.argtypes = [dp, dp, dp, dp, dp, ci, ci, ci, ci, ci, cd, ci, ci]
+        lib.fa_oracle_forward_masked.restype = ci
+        lib.fa_oracle_rows_masked.argtypes = [dp, dp, dp, ip, ci, dp, dp, ci, ci, ci, ci, ci, cd, ci]
+        lib.fa_oracle_rows_masked.restype = ci
         lib.fa_oracle_head_probs.argtypes = [dp, dp, dp, dp, dp, ci, ci, ci, ci, ci, cd, ci, ci]
         lib.fa_oracle_head_probs.restype = ci
         lib.fa_oracle_num_threads.argtypes = []
@@ -79,19 +83,22 @@ def _check_qkv(q, k, v):
     return q, k, v, B, H, Nq, k.shape[1], d
 
 
-def attention(q, k, v, scale: float, row_block: int = 32):
-    """Standard attention for every head and row.  Returns ``(O [B,Nq,H,d] fp64, LSE [B,H,Nq] fp64)``."""
+def attention(q, k, v, scale: float, row_block: int = 32, causal: bool = False):
+    """Standard attention for every head and row.  Returns ``(O [B,Nq,H,d] fp64, LSE [B,H,Nq] fp64)``.
+
+    ``causal`` applies the optional mask of S (Section 2, footnote): row i sees keys j <= i only.
+    """
     q, k, v, B, H, Nq, Nk, d = _check_qkv(q, k, v)
     o = np.empty((B, Nq, H, d), dtype=np.float64)
     lse = np.empty((B, H, Nq), dtype=np.float64)
-    rc = _load().fa_oracle_forward(_dptr(q), _dptr(k), _dptr(v), _dptr(o), _dptr(lse), B, H, Nq, Nk, d,
-                                   float(scale), int(row_block))
+    rc = _load().fa_oracle_forward_masked(_dptr(q), _dptr(k), _dptr(v), _dptr(o), _dptr(lse), B, H, Nq, Nk, d,
+                                          float(scale), int(bool(causal)), int(row_block))
     if rc != 0:
-        raise RuntimeError(f"fa_oracle_forward failed with code {rc}")
+        raise RuntimeError(f"fa_oracle_forward_masked failed with code {rc}")
     return o, lse
 
 
-def attention_rows(q, k, v, scale: float, rows_bhi):
+def attention_rows(q, k, v, scale: float, rows_bhi, causal: bool = False):
     """Standard attention for sampled query rows.
 
     ``rows_bhi`` is an ``[n, 3]`` integer array of (batch, head, row).  Returns
@@ -102,10 +109,11 @@ def attention_rows(q, k, v, scale: float, rows_bhi):
     n = rows.shape[0]
     o = np.empty((n, d), dtype=np.float64)
     lse = np.empty((n,), dtype=np.float64)
-    rc = _load().fa_oracle_rows(_dptr(q), _dptr(k), _dptr(v), rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
-                                n, _dptr(o), _dptr(lse), B, H, Nq, Nk, d, float(scale))
+    rc = _load().fa_oracle_rows_masked(_dptr(q), _dptr(k), _dptr(v),
+                                       rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), n, _dptr(o), _dptr(lse),
+                                       B, H, Nq, Nk, d, float(scale), int(bool(causal)))
     if rc != 0:
-        raise RuntimeError(f"fa_oracle_rows failed with code {rc}")
+        raise RuntimeError(f"fa_oracle_rows_masked failed with code {rc}")
     return o, lse
 
 

@@ -46,8 +46,8 @@ static size_t qkv_index(int b, int n, int h, int k, int N, int H, int d) {
  * rows of the scaled logits and of the softmax.  Follows Algorithm 1 step by step.
  */
 static void attention_row_block(const double* Q, const double* K, const double* V, int H, int Nq, int Nk,
-                                int d, double scale, int b, int h, int i0, int rows, double* S, double* P,
-                                double* O_rows /* rows*d */, double* LSE_rows /* rows */) {
+                                int d, double scale, int causal, int b, int h, int i0, int rows, double* S,
+                                double* P, double* O_rows /* rows*d */, double* LSE_rows /* rows */) {
   /* GEMM-I: S = scale * Q K^T  (Algorithm 1, "Compute S"; the scale sits inside S, Section 2). */
   for (int r = 0; r < rows; ++r) {
     const double* q = Q + qkv_index(b, i0 + r, h, 0, Nq, H, d);
@@ -57,6 +57,13 @@ static void attention_row_block(const double* Q, const double* K, const double* 
       for (int k = 0; k < d; ++k) acc += q[k] * kj[k];
       S[(size_t)r * Nk + j] = scale * acc;
     }
+  }
+  /* Optional masking of S (Section 2, footnote to the attention formula).  Causal mask: query row i sees
+   * keys j <= i only; a masked logit is -infinity, so its softmax weight is exactly zero.  Key 0 is
+   * visible to every row, hence every row keeps a finite maximum. */
+  if (causal) {
+    for (int r = 0; r < rows; ++r)
+      for (int j = i0 + r + 1; j < Nk; ++j) S[(size_t)r * Nk + j] = -INFINITY;
   }
   /* Row softmax of the complete row, shifted by the row maximum (Algorithm 1, the "S - rowmax(S)"
    * and "P = softmax(S)" steps; the shift leaves the softmax unchanged, Section 2).  S itself is
@@ -102,10 +109,11 @@ static int check_shape(const void* Q, const void* K, const void* V, int B, int H
  * rows only to bound the memory of the materialised S and P (2 * row_block * Nk doubles per
  * thread); the arithmetic of a row does not depend on the block size.
  */
-int fa_oracle_forward(const double* Q, const double* K, const double* V, double* O, double* LSE, int B,
-                      int H, int Nq, int Nk, int d, double scale, int row_block) {
+int fa_oracle_forward_masked(const double* Q, const double* K, const double* V, double* O, double* LSE, int B,
+                             int H, int Nq, int Nk, int d, double scale, int causal, int row_block) {
   int rc = check_shape(Q, K, V, B, H, Nq, Nk, d, scale);
   if (rc != ORACLE_OK) return rc;
+  if (causal && Nq != Nk) return ORACLE_ERR_ARG; /* the causal mask is defined for self-attention shapes */
   if (row_block <= 0) row_block = 32;
   if (row_block > Nq) row_block = Nq;
   const int nblk = (Nq + row_block - 1) / row_block;
@@ -133,7 +141,7 @@ int fa_oracle_forward(const double* Q, const double* K, const double* V, double*
         const int b = (int)(t / ((long)nblk * H));
         const int i0 = blk * row_block;
         const int rows = (i0 + row_block <= Nq) ? row_block : (Nq - i0);
-        attention_row_block(Q, K, V, H, Nq, Nk, d, scale, b, h, i0, rows, S, P, Ob, Lb);
+        attention_row_block(Q, K, V, H, Nq, Nk, d, scale, causal, b, h, i0, rows, S, P, Ob, Lb);
         for (int r = 0; r < rows; ++r) {
           if (O) {
             double* dst = O + qkv_index(b, i0 + r, h, 0, Nq, H, d);
@@ -151,15 +159,23 @@ int fa_oracle_forward(const double* Q, const double* K, const double* V, double*
   return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
 }
 
+/* Unmasked forward (the paper's workloads): fa_oracle_forward_masked without a mask. */
+int fa_oracle_forward(const double* Q, const double* K, const double* V, double* O, double* LSE, int B,
+                      int H, int Nq, int Nk, int d, double scale, int row_block) {
+  return fa_oracle_forward_masked(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, 0, row_block);
+}
+
 /*
  * Sampled rows: for t in [0, n_rows) compute query row rows_bhi[3t+2] of head
  * (rows_bhi[3t], rows_bhi[3t+1]).  O_rows is [n_rows][d], LSE_rows is [n_rows].
  * Each sampled row is a complete, two-pass softmax over all Nk keys.
  */
-int fa_oracle_rows(const double* Q, const double* K, const double* V, const int* rows_bhi, int n_rows,
-                   double* O_rows, double* LSE_rows, int B, int H, int Nq, int Nk, int d, double scale) {
+int fa_oracle_rows_masked(const double* Q, const double* K, const double* V, const int* rows_bhi, int n_rows,
+                          double* O_rows, double* LSE_rows, int B, int H, int Nq, int Nk, int d, double scale,
+                          int causal) {
   int rc = check_shape(Q, K, V, B, H, Nq, Nk, d, scale);
   if (rc != ORACLE_OK) return rc;
+  if (causal && Nq != Nk) return ORACLE_ERR_ARG;
   if (n_rows < 0 || (n_rows > 0 && (!rows_bhi || !O_rows || !LSE_rows))) return ORACLE_ERR_ARG;
   for (int t = 0; t < n_rows; ++t) {
     if (rows_bhi[3 * t] < 0 || rows_bhi[3 * t] >= B || rows_bhi[3 * t + 1] < 0 || rows_bhi[3 * t + 1] >= H ||
@@ -182,7 +198,7 @@ int fa_oracle_rows(const double* Q, const double* K, const double* V, const int*
     if (!stop) {
 #pragma omp for schedule(dynamic, 1)
       for (int t = 0; t < n_rows; ++t) {
-        attention_row_block(Q, K, V, H, Nq, Nk, d, scale, rows_bhi[3 * t], rows_bhi[3 * t + 1],
+        attention_row_block(Q, K, V, H, Nq, Nk, d, scale, causal, rows_bhi[3 * t], rows_bhi[3 * t + 1],
                             rows_bhi[3 * t + 2], 1, S, P, O_rows + (size_t)t * d, LSE_rows + t);
       }
     }
@@ -190,6 +206,11 @@ int fa_oracle_rows(const double* Q, const double* K, const double* V, const int*
     free(P);
   }
   return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
+}
+
+int fa_oracle_rows(const double* Q, const double* K, const double* V, const int* rows_bhi, int n_rows,
+                   double* O_rows, double* LSE_rows, int B, int H, int Nq, int Nk, int d, double scale) {
+  return fa_oracle_rows_masked(Q, K, V, rows_bhi, n_rows, O_rows, LSE_rows, B, H, Nq, Nk, d, scale, 0);
 }
 
 /*
@@ -213,7 +234,7 @@ int fa_oracle_head_probs(const double* Q, const double* K, const double* V, doub
   for (int i = 0; i < Nq; ++i) {
     double lse;
     /* recompute the raw scaled logits first: attention_row_block leaves S unshifted. */
-    attention_row_block(Q, K, V, H, Nq, Nk, d, scale, b, h, i, 1, S, P, o, &lse);
+    attention_row_block(Q, K, V, H, Nq, Nk, d, scale, 0, b, h, i, 1, S, P, o, &lse);
     for (int j = 0; j < Nk; ++j) {
       if (S_out) S_out[(size_t)i * Nk + j] = S[j];
       if (P_out) P_out[(size_t)i * Nk + j] = P[j];

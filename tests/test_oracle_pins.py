@@ -314,3 +314,49 @@ def test_oracle_rejects_bad_shapes():
 def test_widen_bit_patterns():
     assert oracle.widen(np.array([0x3C00, 0xC000, 0x0001], dtype=np.uint16), "fp16").tolist() == [1.0, -2.0, 2.0 ** -24]
     assert oracle.widen(np.array([0x3F80, 0xC040, 0x0080], dtype=np.uint16), "bf16").tolist() == [1.0, -3.0, 2.0 ** -126]
+
+
+# ---------------------------------------------------------------- causal mask (optional masking of S, Section 2 footnote)
+def test_causal_rows_equal_unmasked_attention_over_the_prefix():
+    # row i of the causal result is plain attention of q_i over keys 0..i: the unmasked path, pinned above
+    q, k, v = _rand_qkv(21, 2, 23, 2, 6)
+    oc, lc = oracle.attention(q, k, v, 0.6, row_block=5, causal=True)
+    for i in (0, 1, 7, 22):
+        o, l = oracle.attention(q[:, i:i + 1], k[:, :i + 1], v[:, :i + 1], 0.6)
+        np.testing.assert_allclose(oc[:, i:i + 1], o, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(lc[:, :, i:i + 1], l, rtol=1e-13, atol=1e-15)
+    # first row sees only key 0
+    np.testing.assert_allclose(oc[:, 0], v[:, 0], rtol=1e-15)
+    np.testing.assert_allclose(lc[:, :, 0], 0.6 * np.einsum("bhc,bhc->bh", q[:, 0], k[:, 0]), rtol=1e-13, atol=1e-15)
+    # last row sees everything: equals the unmasked result
+    of, lf = oracle.attention(q, k, v, 0.6)
+    np.testing.assert_allclose(oc[:, -1], of[:, -1], rtol=1e-13)
+
+
+def test_causal_against_torch_sdpa_fp64_and_brute_force():
+    import torch
+    q, k, v = _rand_qkv(22, 2, 17, 3, 5)
+    o, lse = oracle.attention(q, k, v, 0.45, causal=True)
+    tq, tk, tv = (torch.from_numpy(x).permute(0, 2, 1, 3) for x in (q, k, v))
+    to = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=0.45, is_causal=True).permute(0, 2, 1, 3)
+    np.testing.assert_allclose(o, to.numpy(), rtol=1e-12, atol=1e-14)
+    # scalar brute force of one head, own loops: sum over j <= i only
+    b, h = 1, 2
+    for i in range(17):
+        s = [0.45 * math.fsum(q[b, i, h, c] * k[b, j, h, c] for c in range(5)) for j in range(i + 1)]
+        den = math.fsum(math.exp(x) for x in s)
+        for c in range(5):
+            assert o[b, i, h, c] == pytest.approx(math.fsum(math.exp(s[j]) / den * v[b, j, h, c] for j in range(i + 1)), rel=1e-12, abs=1e-14)
+        assert lse[b, h, i] == pytest.approx(math.log(den), rel=1e-12, abs=1e-14)
+
+
+def test_causal_sampled_rows_and_shape_check():
+    q, k, v = _rand_qkv(23, 1, 12, 2, 4)
+    o, lse = oracle.attention(q, k, v, 0.5, causal=True)
+    rows = np.array([[0, 0, 0], [0, 1, 11], [0, 1, 5]], dtype=np.int32)
+    orow, lrow = oracle.attention_rows(q, k, v, 0.5, rows, causal=True)
+    for t, (b, h, i) in enumerate(rows):
+        np.testing.assert_allclose(orow[t], o[b, i, h], rtol=1e-14)
+        assert lrow[t] == pytest.approx(lse[b, h, i], rel=1e-14)
+    with pytest.raises(RuntimeError):
+        oracle.attention(q, k[:, :5], v[:, :5], 0.5, causal=True)      # causal needs as many keys as queries
