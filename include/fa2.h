@@ -34,7 +34,8 @@ enum { FA2_FP16 = 0, /* IEEE binary16 */
 enum {
   FA2_OK = 0,
   FA2_ERR_INVALID_ARG = -1, /* NULL Q/K/V/O; B, H, N or d <= 0; scale not finite or <= 0;
-                               a pointer not 16-byte aligned (LSE: 4-byte)            */
+                               a pointer not 16-byte aligned (LSE: 4-byte); an unknown
+                               variant or mask                                        */
   FA2_ERR_UNSUPPORTED = -2, /* d not in {64, 128}; N not a multiple of 128; unknown dtype;
                                a problem too large for 32-bit tile counts             */
   FA2_ERR_LAUNCH = -3       /* the HIP runtime refused the launch                     */
@@ -86,6 +87,26 @@ enum {
  */
 int fa2_fwd_variant(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
                     float scale, int dtype, int variant, void* stream);
+
+/* Masks of S. */
+enum {
+  FA2_MASK_NONE = 0,  /* every query attends to every key                                   */
+  FA2_MASK_CAUSAL = 1 /* query i attends to keys j <= i only (autoregressive / decoder mask) */
+};
+
+/*
+ * fa2_fwd_masked -- fa2_fwd with an optional mask applied to S before the softmax.  Section 2 of the
+ * paper notes that entries of S may be set to -inf ahead of the row-wise softmax; FA2_MASK_CAUSAL does
+ * so for every entry with key index j > query index i, so that
+ *      O_i = softmax(scale * q_i . k_{0..i}) V_{0..i},     LSE[b,h,i] = ln sum_{j<=i} exp(scale * q_i . k_j).
+ * Masked entries contribute exact zeros to P and to the row sum.  The kernel never loads K/V tiles that lie
+ * wholly above the diagonal, so a causal call does about half the work of an unmasked one.
+ *
+ * Arguments, layout, ownership and error behaviour are those of fa2_fwd; `mask` is one of FA2_MASK_*
+ * (anything else: FA2_ERR_INVALID_ARG).  FA2_MASK_NONE is exactly fa2_fwd.
+ */
+int fa2_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
+                   float scale, int dtype, int mask, void* stream);
 
 /* Static, NUL-terminated description of a return code (never NULL). */
 const char* fa2_strerror(int code);

@@ -18,6 +18,8 @@ FA2_VARIANT_AUTO = 0
 FA2_VARIANT_NARROW = 1
 FA2_VARIANT_WIDE = 2
 FA2_VARIANT_NARROW8 = 3
+FA2_MASK_NONE = 0
+FA2_MASK_CAUSAL = 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libfa2.so")
@@ -48,6 +50,8 @@ def load_library():
         lib.fa2_fwd.restype = ci
         lib.fa2_fwd_variant.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, ci, vp]
         lib.fa2_fwd_variant.restype = ci
+        lib.fa2_fwd_masked.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, ci, vp]
+        lib.fa2_fwd_masked.restype = ci
         lib.fa2_strerror.argtypes = [ci]
         lib.fa2_strerror.restype = ctypes.c_char_p
         lib.fa2_version.argtypes = []
@@ -76,13 +80,20 @@ def fa2_fwd_variant_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, N, d, scale, 
                                               float(scale), int(dtype), int(variant), stream))
 
 
+def fa2_fwd_masked_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, N, d, scale, dtype, mask, stream=None) -> int:
+    """Call ``fa2_fwd_masked`` (optional causal mask of S) with raw device addresses; returns the C return code."""
+    return int(load_library().fa2_fwd_masked(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, int(B), int(H), int(N), int(d),
+                                             float(scale), int(dtype), int(mask), stream))
+
+
 def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, stream=None,
-            variant: int = FA2_VARIANT_AUTO):
+            variant: int = FA2_VARIANT_AUTO, causal: bool = False):
     """Attention forward on torch CUDA tensors ``[B, N, H, d]`` (fp16 or bf16, contiguous).
 
     Returns ``(O, LSE)`` with O like ``q`` and LSE ``[B, H, N]`` fp32 (``None`` if ``return_lse`` is
     false).  The kernel is enqueued on ``stream`` (a ``torch.cuda.Stream``) or on torch's current stream.
     ``variant`` selects the tile shape (``FA2_VARIANT_*``); the default lets the library choose.
+    ``causal`` masks S so that query i sees keys j <= i only (``fa2_fwd_masked``; default tile shape only).
     """
     import torch
 
@@ -114,9 +125,13 @@ def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, 
         lse = None
     with torch.cuda.device(q.device):
         s = stream if stream is not None else torch.cuda.current_stream()
-        rc = fa2_fwd_variant_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                 None if lse is None else lse.data_ptr(), B, H, N, d, scale, dtype, variant,
-                                 s.cuda_stream)
+        ptrs = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), None if lse is None else lse.data_ptr())
+        if causal:
+            if variant != FA2_VARIANT_AUTO:
+                raise ValueError("the causal mask runs on the library's default tile shape only")
+            rc = fa2_fwd_masked_raw(*ptrs, B, H, N, d, scale, dtype, FA2_MASK_CAUSAL, s.cuda_stream)
+        else:
+            rc = fa2_fwd_variant_raw(*ptrs, B, H, N, d, scale, dtype, variant, s.cuda_stream)
     if rc != FA2_OK:
         raise Fa2Error(rc, fa2_strerror(rc))
     return out, lse

@@ -140,7 +140,12 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 //   8 wavefronts, 4 buffers: 256 rows per workgroup, 1 workgroup per CU, global loads issued three
 //                            tiles ahead and half the L2->LDS traffic per FLOP.
 // Either way a SIMD runs two wavefronts, so one wavefront's softmax arithmetic overlaps the other's MFMAs.
-template <int DT, int D, int kWv, int kNBuf>
+//
+// kCausal applies the optional mask of S (Section 2 of the paper: entries of S may be set to -inf before the
+// softmax; here those with key index > query index).  A Q tile then stops at its diagonal: it visits
+// (qt+1)*kNBuf K/V tiles instead of N/kBc, only the last kNBuf of them straddle the diagonal and need the
+// element-wise mask, and Q tiles are dealt heaviest first.
+template <int DT, int D, int kWv, int kNBuf, bool kCausal>
 __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(const uint16_t* __restrict__ Q,
                                                                              const uint16_t* __restrict__ K,
                                                                              const uint16_t* __restrict__ V,
@@ -154,6 +159,7 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
   using std::true_type;
   static_assert(kNBuf == 2 || kNBuf == 4, "two or four LDS buffers per operand");
   constexpr int kRows = 32 * kWv;   // query rows per workgroup
+  static_assert(kRows == kNBuf * kBc, "a Q tile spans exactly kNBuf K/V tiles (the causal tile count relies on it)");
   constexpr int kKSteps = D / 16;   // MFMA steps along d for S^T = K Q^T
   constexpr int kDBlocks = D / 32;  // 32-row blocks of O^T
   constexpr int kKBlocks = kBc / 32;  // 32-key blocks of S^T
@@ -191,7 +197,8 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
     tile = xcd * per + (xcd < rem ? xcd : rem) + idx;
   }
   const int bh = tile / n_qtiles;
-  const int qt = tile - bh * n_qtiles;
+  // Under the causal mask the work of a Q tile grows with its index: within a head the last tile goes first.
+  const int qt = kCausal ? n_qtiles - 1 - (tile - bh * n_qtiles) : tile - bh * n_qtiles;
   const int b = bh / H;
   const int h = bh - b * H;
 
@@ -297,7 +304,20 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
   // S_j, O += P~_j V_j, then S_{j+1} = K_{j+1} Q^T.  Every iteration thus has one block of softmax
   // arithmetic and one block of back-to-back MFMAs, which the two wavefronts sharing a SIMD overlap.
   // kNext: a tile j+1 exists.
-  auto iteration = [&](auto next_tag, const uint16_t* v_cur, const uint16_t* k_next) __attribute__((always_inline)) {
+  // mask_tag: the tile straddles the causal diagonal; `visible` is then the largest value of
+  // 32 kb + 8 (v/4) + v%4 (the key's position in the tile minus this half's 4 hh) that register v of key
+  // block kb may have for its key to be at or before this lane's query.
+  auto iteration = [&](auto next_tag, auto mask_tag, int visible, const uint16_t* v_cur,
+                       const uint16_t* k_next) __attribute__((always_inline)) {
+    if constexpr (decltype(mask_tag)::value) {
+      // S_ij = -inf for j > i: the exponential below turns it into an exact 0 in P~ and in the rowsum.  Key 0
+      // is visible to every query, so the reference point is finite from the first tile on.
+#pragma unroll
+      for (int kb = 0; kb < kKBlocks; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (32 * kb + 8 * (v / 4) + (v % 4) > visible) st[kb][v] = -INFINITY;
+    }
     // ---- online softmax for this lane's query (Algorithm 2: rowmax, P~, rowsum, rescale) ----
     // The maximum is taken on the unscaled logits (valid for scale > 0) and the scale is folded into
     // the exponent: exp(scale*(s - m)) = exp2(s*c - m*c) with c = scale*log2(e).
@@ -316,7 +336,10 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
     if (__builtin_amdgcn_ballot_w64(move) != 0) {
       const float m_new = move ? mx : m_ref;
       const float mc_new = m_new * scale_log2e;
-      const float alpha = __builtin_amdgcn_exp2f(mc_ref - mc_new);  // exp(m_old - m_new); 0 on the first tile
+      // exp(m_old - m_new); 0 on the first tile.  A lane whose own row does not move (the branch is taken when
+      // any lane of the wavefront moves) gets exactly 1, not exp2 of a contracted m*c - m*c that may differ from
+      // 0 in the last bit: a row's result must not depend on what other rows of the wavefront see.
+      const float alpha = move ? __builtin_amdgcn_exp2f(mc_ref - mc_new) : 1.0f;
       m_ref = m_new;
       mc_ref = mc_new;
       l_run *= alpha;
@@ -396,7 +419,8 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
   constexpr int kWaitRelaxed = (kRelaxedVmcnt & 15) | ((kRelaxedVmcnt >> 4) << 14) | 0x0F70;
   constexpr int kWaitAll = 0x0F70;  // vmcnt(0), expcnt and lgkmcnt left alone
 
-  const int n_tiles = N / kBc;  // a multiple of kNBuf (N is a multiple of 32*kWv)
+  // a multiple of kNBuf either way (N is a multiple of 32*kWv); causal: the keys up to the end of this Q tile
+  const int n_tiles = kCausal ? (qt + 1) * kNBuf : N / kBc;
   uint16_t* const k_buf[4] = {k_lds0, k_lds1, k_lds2, k_lds3};
   uint16_t* const v_buf[4] = {v_lds0, v_lds1, v_lds2, v_lds3};
   static_for<kNBuf>([&](auto t) { stage_in(true_type{}, k_rsrc, decltype(t)::value, k_buf[decltype(t)::value]); });
@@ -424,18 +448,21 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
   for (; j + kNBuf < n_tiles; j += kNBuf) {  // every barrier of these iterations issues its full set of loads
     static_for<kNBuf>([&](auto t) {
       constexpr int i = decltype(t)::value;
-      iteration(true_type{}, v_buf[i], k_buf[(i + 1) % kNBuf]);
+      iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf]);
       boundary(true_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
     });
   }
-  // last kNBuf tiles: wait for everything, and the very last tile has no successor
+  // last kNBuf tiles: wait for everything, and the very last tile has no successor.  Under the causal mask
+  // these are exactly the tiles of this Q tile's own rows, the ones the diagonal crosses.
+  using mask_tail = std::integral_constant<bool, kCausal>;
   static_for<kNBuf>([&](auto t) {
     constexpr int i = decltype(t)::value;
+    const int visible = wave * 32 + r - 4 * hh - i * kBc;  // (q_row - first key of tile j+i) - 4 hh
     if constexpr (i + 1 < kNBuf) {
-      iteration(true_type{}, v_buf[i], k_buf[(i + 1) % kNBuf]);
+      iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
       boundary(false_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
     } else {
-      iteration(false_type{}, v_buf[i], k_buf[(i + 1) % kNBuf]);
+      iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
     }
   });
 
@@ -659,7 +686,7 @@ __global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_
           move[half] = (mx[half] - m_ref[half]) * scale_log2e > kLazyLog2;
           const float m_new = move[half] ? mx[half] : m_ref[half];
           const float mc_new = m_new * scale_log2e;
-          alpha_pend[half] = __builtin_amdgcn_exp2f(mc_ref[half] - mc_new);
+          alpha_pend[half] = move[half] ? __builtin_amdgcn_exp2f(mc_ref[half] - mc_new) : 1.0f;  // exactly 1 for a row that stays
           m_ref[half] = m_new;
           mc_ref[half] = mc_new;
           l_run[half] *= alpha_pend[half];
@@ -813,25 +840,30 @@ __global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_
 
 template <int DT, int D>
 int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, float scale,
-           int variant, hipStream_t stream) {
+           int variant, int mask, hipStream_t stream) {
   const float scale_log2e = scale * 1.44269504088896340736f;
   const bool wide = variant == FA2_VARIANT_WIDE;
   const bool rows256 = variant == FA2_VARIANT_WIDE || variant == FA2_VARIANT_NARROW8;
   const int n_qtiles = N / (rows256 ? kWideBr : kBr);
   const long long total = (long long)B * H * n_qtiles;
   if (total > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
-  if (wide) {
+  if (mask == FA2_MASK_CAUSAL) {  // 128-row shape only (checked by the caller)
+    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, true>), dim3((unsigned)total), dim3(kThreads), 0, stream,
+                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
+                       n_qtiles, (int)total);
+  } else if (wide) {
     hipLaunchKernelGGL((fa2_fwd_wide_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                        static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
                        n_qtiles, (int)total);
   } else if (variant == FA2_VARIANT_NARROW8) {
-    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 8, 4>), dim3((unsigned)total), dim3(512), 0, stream,
+    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 8, 4, false>), dim3((unsigned)total), dim3(512), 0, stream,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                        static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
                        n_qtiles, (int)total);
   } else {
-    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2>), dim3((unsigned)total), dim3(kThreads), 0, stream,
+    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, false>), dim3((unsigned)total), dim3(kThreads), 0, stream,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                        static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
                        n_qtiles, (int)total);
@@ -843,8 +875,9 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 
 }  // namespace
 
-extern "C" int fa2_fwd_variant(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N,
-                               int d, float scale, int dtype, int variant, void* stream) {
+namespace {
+int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d, float scale,
+        int dtype, int variant, int mask, void* stream) {
   // All validation happens before the first HIP call: an error launches nothing.
   if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return FA2_ERR_INVALID_ARG;
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return FA2_ERR_INVALID_ARG;
@@ -854,6 +887,7 @@ extern "C" int fa2_fwd_variant(const void* Q, const void* K, const void* V, void
   if (variant != FA2_VARIANT_AUTO && variant != FA2_VARIANT_NARROW && variant != FA2_VARIANT_WIDE &&
       variant != FA2_VARIANT_NARROW8)
     return FA2_ERR_INVALID_ARG;
+  if (mask != FA2_MASK_NONE && mask != FA2_MASK_CAUSAL) return FA2_ERR_INVALID_ARG;
   if (dtype != FA2_FP16 && dtype != FA2_BF16) return FA2_ERR_UNSUPPORTED;
   if (d != 64 && d != 128) return FA2_ERR_UNSUPPORTED;
   if (N % kBr != 0) return FA2_ERR_UNSUPPORTED;
@@ -867,28 +901,40 @@ extern "C" int fa2_fwd_variant(const void* Q, const void* K, const void* V, void
     // every workload shape tried (N = 512 .. 16384, d = 64 and 128); the others stay selectable for sweeps.
     variant = FA2_VARIANT_NARROW;
   }
+  if (mask == FA2_MASK_CAUSAL && variant != FA2_VARIANT_NARROW) return FA2_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
-    return d == 64 ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, s)
-                   : launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, s);
+    return d == 64 ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
+                   : launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
   }
-  return d == 64 ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, s)
-                 : launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, s);
+  return d == 64 ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
+                 : launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
+}
+}  // namespace
+
+extern "C" int fa2_fwd_variant(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N,
+                               int d, float scale, int dtype, int variant, void* stream) {
+  return run(Q, K, V, O, LSE, B, H, N, d, scale, dtype, variant, FA2_MASK_NONE, stream);
+}
+
+extern "C" int fa2_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N,
+                              int d, float scale, int dtype, int mask, void* stream) {
+  return run(Q, K, V, O, LSE, B, H, N, d, scale, dtype, FA2_VARIANT_AUTO, mask, stream);
 }
 
 extern "C" int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
                        float scale, int dtype, void* stream) {
-  return fa2_fwd_variant(Q, K, V, O, LSE, B, H, N, d, scale, dtype, FA2_VARIANT_AUTO, stream);
+  return run(Q, K, V, O, LSE, B, H, N, d, scale, dtype, FA2_VARIANT_AUTO, FA2_MASK_NONE, stream);
 }
 
 extern "C" const char* fa2_strerror(int code) {
   switch (code) {
     case FA2_OK: return "success";
-    case FA2_ERR_INVALID_ARG: return "invalid argument (NULL or misaligned pointer, non-positive size, or scale not finite and > 0)";
+    case FA2_ERR_INVALID_ARG: return "invalid argument (NULL or misaligned pointer, non-positive size, scale not finite and > 0, or unknown variant or mask)";
     case FA2_ERR_UNSUPPORTED: return "unsupported problem (d must be 64 or 128, N a multiple of 128, dtype fp16 or bf16)";
     case FA2_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     default: return "unknown fa2 error code";
   }
 }
 
-extern "C" int fa2_version(void) { return 100; /* 0.1.0 */ }
+extern "C" int fa2_version(void) { return 200; /* 0.2.0 */ }

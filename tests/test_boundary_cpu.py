@@ -18,7 +18,7 @@ def _declared_functions():
 
 
 def test_header_declares_the_boundary():
-    assert {"fa2_fwd", "fa2_strerror", "fa2_version"} <= set(_declared_functions())
+    assert {"fa2_fwd", "fa2_fwd_variant", "fa2_fwd_masked", "fa2_strerror", "fa2_version"} <= set(_declared_functions())
 
 
 def test_library_exports_every_declared_symbol():
@@ -63,6 +63,42 @@ def test_bad_arguments_are_rejected_without_a_launch(args, code):
     a = dict(q=P, k=P, v=P, o=P, lse=P, B=1, H=2, N=256, d=64, scale=0.125, dtype=fa2.FA2_FP16)
     a.update(args)
     rc = fa2.fa2_fwd_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["N"], a["d"], a["scale"], a["dtype"])
+    assert rc == code
+
+
+_OKARGS = dict(q=P, k=P, v=P, o=P, lse=P, B=1, H=2, N=256, d=64, scale=0.125, dtype=fa2.FA2_FP16)
+
+
+@pytest.mark.parametrize("variant,args,code", [
+    (99, {}, fa2.FA2_ERR_INVALID_ARG),                                 # unknown tile shape
+    (-1, {}, fa2.FA2_ERR_INVALID_ARG),
+    (fa2.FA2_VARIANT_WIDE, dict(N=384), fa2.FA2_ERR_UNSUPPORTED),      # 256-row shapes need N % 256 == 0
+    (fa2.FA2_VARIANT_NARROW8, dict(N=128), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_VARIANT_NARROW, dict(d=32), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_VARIANT_NARROW, dict(q=None), fa2.FA2_ERR_INVALID_ARG),
+])
+def test_variant_entry_rejects_bad_arguments_without_a_launch(variant, args, code):
+    a = dict(_OKARGS)
+    a.update(args)
+    rc = fa2.fa2_fwd_variant_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["N"], a["d"], a["scale"],
+                                 a["dtype"], variant)
+    assert rc == code
+
+
+@pytest.mark.parametrize("mask,args,code", [
+    (2, {}, fa2.FA2_ERR_INVALID_ARG),                                  # unknown mask
+    (-1, {}, fa2.FA2_ERR_INVALID_ARG),
+    (fa2.FA2_MASK_CAUSAL, dict(k=None), fa2.FA2_ERR_INVALID_ARG),
+    (fa2.FA2_MASK_CAUSAL, dict(N=192), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_MASK_CAUSAL, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_MASK_CAUSAL, dict(scale=-1.0), fa2.FA2_ERR_INVALID_ARG),
+    (fa2.FA2_MASK_NONE, dict(dtype=3), fa2.FA2_ERR_UNSUPPORTED),
+])
+def test_masked_entry_rejects_bad_arguments_without_a_launch(mask, args, code):
+    a = dict(_OKARGS)
+    a.update(args)
+    rc = fa2.fa2_fwd_masked_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["N"], a["d"], a["scale"],
+                                a["dtype"], mask)
     assert rc == code
 
 
