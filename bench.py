@@ -44,7 +44,7 @@ def _device_tensors(index):
     return w, q, k, v
 
 
-def _time_workload(index, steps, warmup):
+def _time_workload(index, steps, warmup, causal=False):
     """Times `steps` back-to-back launches with HIP events on the launch stream; returns ms per step."""
     import torch
     import paper_2312_11918_amd as fa2
@@ -54,13 +54,13 @@ def _time_workload(index, steps, warmup):
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
-        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream)
+        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream, causal=causal)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record(stream)
     for _ in range(steps):
-        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream)
+        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream, causal=causal)
     e1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -150,6 +150,14 @@ def main():
                                      "frac_mfma_peak": round(tf / MFMA_PEAK_TFLOPS, 4),
                                      "hbm_gbs_algorithmic": round((4 * wi.B * wi.H * wi.N * wi.d * 2 + 4 * wi.B * wi.H * wi.N) / (msi * 1e-3) / 1e9, 1)}
 
+    # the same shape under the causal mask (fa2_fwd_masked); FLOPs counted as half of the unmasked product
+    causal = None
+    if not args.only_headline:
+        _, cms, _ = _time_workload(args.workload, args.steps, args.warmup, causal=True)
+        ctf = 0.5 * w.flops / (cms * 1e-3) / 1e12
+        causal = {"ms": round(cms, 5), "tflops": round(ctf, 2), "frac_mfma_peak": round(ctf / MFMA_PEAK_TFLOPS, 4),
+                  "flops_counted": "2*B*H*N^2*d"}
+
     out = {
         "metric": "attention fwd TFLOP/s (4*B*H*N^2*d)",
         "value": round(tflops, 2),
@@ -172,6 +180,7 @@ def main():
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_hbm_bytes_per_launch": alg_bytes,
                      "kernel": "fa2_fwd_kernel", "kernel_ms": round(ms, 5)},
         "workloads": per_workload,
+        "causal_same_shape": causal,
         "paper_context": "H100 PCIe, fp16: 295.7 TFLOP/s best at d=128 (Table 1), 39% of its 756 TFLOP/s peak; not a target",
     }
     if not args.no_cpu_baseline:

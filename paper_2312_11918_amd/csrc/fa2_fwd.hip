@@ -196,24 +196,23 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
     const int xcd = wg % kXcds, idx = wg / kXcds;
     tile = xcd * per + (xcd < rem ? xcd : rem) + idx;
   }
-  const int bh = tile / n_qtiles;
-  // Under the causal mask the work of a Q tile grows with its index: within a head the last tile goes first.
-  const int qt = kCausal ? n_qtiles - 1 - (tile - bh * n_qtiles) : tile - bh * n_qtiles;
+  // Under the causal mask the work of Q tile qt grows like qt + 1, so a workgroup takes a PAIR of Q tiles of
+  // one head, n_qtiles-1-p and then p, one after the other: every workgroup then does the same amount of
+  // work (but for the unpaired middle tile when n_qtiles is odd).  total_tiles counts pairs in that case.
+  const int n_items = kCausal ? (n_qtiles + 1) / 2 : n_qtiles;
+  const int bh = tile / n_items;
+  const int item = tile - bh * n_items;
   const int b = bh / H;
   const int h = bh - b * H;
+  const int n_pass = (kCausal && item != n_qtiles - 1 - item) ? 2 : 1;
+  int qt, q_row, n_tiles;  // set per pass
 
   const size_t row_stride = (size_t)H * D;                          // elements between consecutive tokens
   const size_t head_base = ((size_t)b * N * H + (size_t)h) * D;     // element (b, 0, h, 0)
   const size_t tile_stride = (size_t)kBc * row_stride;              // elements between consecutive K/V tiles
-  const int q_row = qt * kRows + wave * 32 + r;
 
   // Q_i fragment, held in registers for the whole loop: B operand of S^T = K Q^T.
   u32x4 qf[kKSteps];
-  {
-    const uint16_t* qp = Q + head_base + (size_t)q_row * row_stride + 8 * hh;
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
-  }
 
   // Direct global->LDS staging (buffer_load ... lds).  Wavefront w issues loads number w*kLoadsPerWave + i
   // of a tile; load n fills LDS bytes [1024 n, 1024 n + 1024) of the tile, lane l the 16-byte chunk
@@ -260,14 +259,10 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
   // Accumulators of Algorithm 2: O^T (fp32), the rowmax reference and the running rowsum.  Each half
   // of the wavefront keeps the partial rowsum of its own keys; the two are added in the epilogue.
   f32x16 ot[kDBlocks];
-#pragma unroll
-  for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) ot[db][v] = 0.f;
-  f32x16 st[kKBlocks];       // S^T of the tile being processed
-  float m_ref = -INFINITY;   // reference point of the exponentials, in units of the unscaled logits q.k
-  float mc_ref = -INFINITY;  // m_ref * scale * log2(e)
-  float l_run = 0.f;
+  f32x16 st[kKBlocks];  // S^T of the tile being processed
+  float m_ref;          // reference point of the exponentials, in units of the unscaled logits q.k
+  float mc_ref;         // m_ref * scale * log2(e)
+  float l_run;
 
   // Operand fragment of MFMA step `step` of GEMM-I (K rows) / GEMM-II (V columns, transposed by the load).
   auto k_frag = [&](const uint16_t* kt, int step) __attribute__((always_inline)) -> u32x4 {
@@ -419,21 +414,8 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
   constexpr int kWaitRelaxed = (kRelaxedVmcnt & 15) | ((kRelaxedVmcnt >> 4) << 14) | 0x0F70;
   constexpr int kWaitAll = 0x0F70;  // vmcnt(0), expcnt and lgkmcnt left alone
 
-  // a multiple of kNBuf either way (N is a multiple of 32*kWv); causal: the keys up to the end of this Q tile
-  const int n_tiles = kCausal ? (qt + 1) * kNBuf : N / kBc;
   uint16_t* const k_buf[4] = {k_lds0, k_lds1, k_lds2, k_lds3};
   uint16_t* const v_buf[4] = {v_lds0, v_lds1, v_lds2, v_lds3};
-  static_for<kNBuf>([&](auto t) { stage_in(true_type{}, k_rsrc, decltype(t)::value, k_buf[decltype(t)::value]); });
-  static_for<kNBuf - 1>([&](auto t) { stage_in(false_type{}, v_rsrc, decltype(t)::value, v_buf[decltype(t)::value]); });
-  // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
-#pragma unroll
-  for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
-  __builtin_amdgcn_s_waitcnt(kWaitAll);
-  __syncthreads();
-  gemm1(k_lds0);
-  __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
-  if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
-  if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
 
   // end of iteration j: publish what iteration j+1 reads, then refill the two dead buffers
   auto boundary = [&](auto relaxed_tag, int j, uint16_t* k_fill, uint16_t* v_fill) __attribute__((always_inline)) {
@@ -444,45 +426,77 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
     if (j + kNBuf < n_tiles) stage_in(false_type{}, v_rsrc, j + kNBuf, v_fill);
   };
 
-  int j = 0;
-  for (; j + kNBuf < n_tiles; j += kNBuf) {  // every barrier of these iterations issues its full set of loads
+  for (int pass = 0; pass < n_pass; ++pass) {
+    if (pass > 0) __syncthreads();  // the first Q tile's last K/V reads are over before the buffers are refilled
+    qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
+    q_row = qt * kRows + wave * 32 + r;
+    // a multiple of kNBuf either way (N is a multiple of 32*kWv); causal: the keys up to the end of this Q tile
+    n_tiles = kCausal ? (qt + 1) * kNBuf : N / kBc;
+    {
+      const uint16_t* qp = Q + head_base + (size_t)q_row * row_stride + 8 * hh;
+#pragma unroll
+      for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+    }
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) ot[db][v] = 0.f;
+    m_ref = -INFINITY;
+    mc_ref = -INFINITY;
+    l_run = 0.f;
+
+    static_for<kNBuf>([&](auto t) { stage_in(true_type{}, k_rsrc, decltype(t)::value, k_buf[decltype(t)::value]); });
+    static_for<kNBuf - 1>([&](auto t) { stage_in(false_type{}, v_rsrc, decltype(t)::value, v_buf[decltype(t)::value]); });
+    // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+    __builtin_amdgcn_s_waitcnt(kWaitAll);
+    __syncthreads();
+    gemm1(k_lds0);
+    __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
+    if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
+    if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
+
+    int j = 0;
+    for (; j + kNBuf < n_tiles; j += kNBuf) {  // every barrier of these iterations issues its full set of loads
+      static_for<kNBuf>([&](auto t) {
+        constexpr int i = decltype(t)::value;
+        iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf]);
+        boundary(true_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
+      });
+    }
+    // last kNBuf tiles: wait for everything, and the very last tile has no successor.  Under the causal mask
+    // these are exactly the tiles of this Q tile's own rows, the ones the diagonal crosses.
+    using mask_tail = std::integral_constant<bool, kCausal>;
     static_for<kNBuf>([&](auto t) {
       constexpr int i = decltype(t)::value;
-      iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf]);
-      boundary(true_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
+      const int visible = wave * 32 + r - 4 * hh - i * kBc;  // (q_row - first key of tile j+i) - 4 hh
+      if constexpr (i + 1 < kNBuf) {
+        iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
+        boundary(false_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
+      } else {
+        iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
+      }
     });
-  }
-  // last kNBuf tiles: wait for everything, and the very last tile has no successor.  Under the causal mask
-  // these are exactly the tiles of this Q tile's own rows, the ones the diagonal crosses.
-  using mask_tail = std::integral_constant<bool, kCausal>;
-  static_for<kNBuf>([&](auto t) {
-    constexpr int i = decltype(t)::value;
-    const int visible = wave * 32 + r - 4 * hh - i * kBc;  // (q_row - first key of tile j+i) - 4 hh
-    if constexpr (i + 1 < kNBuf) {
-      iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
-      boundary(false_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
-    } else {
-      iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
-    }
-  });
 
-  // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
-  const float l_tot = sum_with_partner_half(l_run);
-  const float inv_l = 1.0f / l_tot;
-  uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
+    // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
+    const float l_tot = sum_with_partner_half(l_run);
+    const float inv_l = 1.0f / l_tot;
+    uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
 #pragma unroll
-  for (int db = 0; db < kDBlocks; ++db) {
+    for (int db = 0; db < kDBlocks; ++db) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      // accumulator registers 4g..4g+3 hold d = 32 db + 8 g + 4 hh + (0..3) of this lane's query
-      u32x2 w = {E::pack2(ot[db][4 * g + 0] * inv_l, ot[db][4 * g + 1] * inv_l),
-                 E::pack2(ot[db][4 * g + 2] * inv_l, ot[db][4 * g + 3] * inv_l)};
-      *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
+      for (int g = 0; g < 4; ++g) {
+        // accumulator registers 4g..4g+3 hold d = 32 db + 8 g + 4 hh + (0..3) of this lane's query
+        u32x2 w = {E::pack2(ot[db][4 * g + 0] * inv_l, ot[db][4 * g + 1] * inv_l),
+                   E::pack2(ot[db][4 * g + 2] * inv_l, ot[db][4 * g + 3] * inv_l)};
+        *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
+      }
     }
-  }
-  if (LSE != nullptr && hh == 0) {
-    LSE[((size_t)b * H + h) * N + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
-  }
+    if (LSE != nullptr && hh == 0) {
+      LSE[((size_t)b * H + h) * N + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
+    }
+  }  // pass
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -495,7 +509,6 @@ __global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(con
 // overlap of softmax arithmetic with the matrix cores has to happen inside the instruction stream of
 // that one wavefront: the loop is software-pipelined over STAGES of 32 keys,
 //     stage s:   matrix cores:  S_{s+1} = K_{s+1} Q^T   and   O += P~_{s-1} V_{s-1}
-//                vector ALU:    online softmax of S_s -> P~_s
 // and the softmax is cut into small chunks that are placed between the MFMAs in program order, so
 // they issue in the shadow of the 8-pass MFMAs.  (The paper's Section 6 overlaps copies with the two
 // GEMMs and leaves the softmax exposed; its register-pressure discussion in Section 7 is the same
@@ -845,7 +858,8 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   const bool wide = variant == FA2_VARIANT_WIDE;
   const bool rows256 = variant == FA2_VARIANT_WIDE || variant == FA2_VARIANT_NARROW8;
   const int n_qtiles = N / (rows256 ? kWideBr : kBr);
-  const long long total = (long long)B * H * n_qtiles;
+  // causal: one workgroup per pair of Q tiles (n_qtiles-1-p, p)
+  const long long total = (long long)B * H * (mask == FA2_MASK_CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles);
   if (total > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
   if (mask == FA2_MASK_CAUSAL) {  // 128-row shape only (checked by the caller)
     hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, true>), dim3((unsigned)total), dim3(kThreads), 0, stream,
