@@ -126,8 +126,8 @@ template <int D> struct Tile {
   static constexpr int kChunksPerRow = D / 8;                      // 16-byte chunks per row
   static constexpr int kElems = kBc * D;                           // elements per tile
   static constexpr int kLoadsPerWave = kElems * 2 / 1024 / kWaves; // 1 KiB wavefront loads per tile and wave
-  static __device__ __forceinline__ int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
-  static __device__ __forceinline__ int swz_v(int row) { return (D == 128 ? (row & 3) : ((row >> 1) & 1)) << 2; }
+  static __device__ __forceinline__ int swz_k(int row) { return D >= 128 ? (row & 15) : ((row >> 1) & 7); }
+  static __device__ __forceinline__ int swz_v(int row) { return (D >= 128 ? (row & 3) : ((row >> 1) & 1)) << 2; }
 };
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -146,7 +146,7 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 // (qt+1)*kNBuf K/V tiles instead of N/kBc, only the last kNBuf of them straddle the diagonal and need the
 // element-wise mask, and Q tiles are dealt heaviest first.
 template <int DT, int D, int kWv, int kNBuf, bool kCausal>
-__global__ __launch_bounds__(kWv * 64, kWv == 4 ? 2 : 1) void fa2_fwd_kernel(const uint16_t* __restrict__ Q,
+__global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_fwd_kernel(const uint16_t* __restrict__ Q,
                                                                              const uint16_t* __restrict__ K,
                                                                              const uint16_t* __restrict__ V,
                                                                              uint16_t* __restrict__ O,
@@ -866,6 +866,11 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                        static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
                        n_qtiles, (int)total);
+  } else if constexpr (D == 256) {  // one tile shape at this head dimension (checked by the caller)
+    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, false>), dim3((unsigned)total), dim3(kThreads), 0, stream,
+                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
+                       n_qtiles, (int)total);
   } else if (wide) {
     hipLaunchKernelGGL((fa2_fwd_wide_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
@@ -903,7 +908,7 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
     return FA2_ERR_INVALID_ARG;
   if (mask != FA2_MASK_NONE && mask != FA2_MASK_CAUSAL) return FA2_ERR_INVALID_ARG;
   if (dtype != FA2_FP16 && dtype != FA2_BF16) return FA2_ERR_UNSUPPORTED;
-  if (d != 64 && d != 128) return FA2_ERR_UNSUPPORTED;
+  if (d != 64 && d != 128 && d != 256) return FA2_ERR_UNSUPPORTED;
   if (N % kBr != 0) return FA2_ERR_UNSUPPORTED;
   if ((variant == FA2_VARIANT_WIDE || variant == FA2_VARIANT_NARROW8) && N % kWideBr != 0) return FA2_ERR_UNSUPPORTED;
   // element offsets are computed in 64 bits; the row index b*N+n must still fit the tile arithmetic
@@ -916,13 +921,16 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
     variant = FA2_VARIANT_NARROW;
   }
   if (mask == FA2_MASK_CAUSAL && variant != FA2_VARIANT_NARROW) return FA2_ERR_UNSUPPORTED;
+  if (d == 256 && variant != FA2_VARIANT_NARROW) return FA2_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
-    return d == 64 ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
-                   : launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
+    return d == 64    ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
+           : d == 128 ? launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
+                      : launch<FA2_FP16, 256>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
   }
-  return d == 64 ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
-                 : launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
+  return d == 64    ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
+         : d == 128 ? launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
+                    : launch<FA2_BF16, 256>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
 }
 }  // namespace
 

@@ -53,7 +53,7 @@ P = 0x1000  # a 16-byte aligned, never dereferenced "device address": validation
     (dict(o=P + 2), fa2.FA2_ERR_INVALID_ARG),
     (dict(lse=P + 2), fa2.FA2_ERR_INVALID_ARG),
     (dict(d=96), fa2.FA2_ERR_UNSUPPORTED),
-    (dict(d=256), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(d=512), fa2.FA2_ERR_UNSUPPORTED),
     (dict(N=100), fa2.FA2_ERR_UNSUPPORTED),
     (dict(N=64), fa2.FA2_ERR_UNSUPPORTED),
     (dict(dtype=7), fa2.FA2_ERR_UNSUPPORTED),
@@ -75,6 +75,8 @@ _OKARGS = dict(q=P, k=P, v=P, o=P, lse=P, B=1, H=2, N=256, d=64, scale=0.125, dt
     (fa2.FA2_VARIANT_WIDE, dict(N=384), fa2.FA2_ERR_UNSUPPORTED),      # 256-row shapes need N % 256 == 0
     (fa2.FA2_VARIANT_NARROW8, dict(N=128), fa2.FA2_ERR_UNSUPPORTED),
     (fa2.FA2_VARIANT_NARROW, dict(d=32), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_VARIANT_WIDE, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),      # d=256 runs on the 128-row shape only
+    (fa2.FA2_VARIANT_NARROW8, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),
     (fa2.FA2_VARIANT_NARROW, dict(q=None), fa2.FA2_ERR_INVALID_ARG),
 ])
 def test_variant_entry_rejects_bad_arguments_without_a_launch(variant, args, code):
@@ -90,7 +92,7 @@ def test_variant_entry_rejects_bad_arguments_without_a_launch(variant, args, cod
     (-1, {}, fa2.FA2_ERR_INVALID_ARG),
     (fa2.FA2_MASK_CAUSAL, dict(k=None), fa2.FA2_ERR_INVALID_ARG),
     (fa2.FA2_MASK_CAUSAL, dict(N=192), fa2.FA2_ERR_UNSUPPORTED),
-    (fa2.FA2_MASK_CAUSAL, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_MASK_CAUSAL, dict(d=96), fa2.FA2_ERR_UNSUPPORTED),
     (fa2.FA2_MASK_CAUSAL, dict(scale=-1.0), fa2.FA2_ERR_INVALID_ARG),
     (fa2.FA2_MASK_NONE, dict(dtype=3), fa2.FA2_ERR_UNSUPPORTED),
 ])

@@ -56,6 +56,8 @@ def _check(o_gpu, lse_gpu, o_ref, lse_ref, what):
     (1, 3, 896, 128, "bf16", 0.0),
     (1, 5, 1152, 64, "bf16", 0.0),    # 45 workgroups: not a multiple of the 8 XCDs
     (3, 1, 1024, 128, "fp16", 0.0),
+    (1, 2, 384, 256, "fp16", 0.0),    # d = 256
+    (2, 1, 512, 256, "bf16", 0.0),
 ])
 def test_causal_parity_elementwise(B, H, N, d, dtype, outliers):
     seed = 3000 + 5 * N + d + B

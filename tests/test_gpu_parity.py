@@ -57,6 +57,9 @@ def _check(o_gpu, lse_gpu, o_ref, lse_ref, what):
     (1, 3, 896, 128, "bf16"),     # 7 query tiles, 14 key tiles
     (1, 5, 1152, 64, "bf16"),     # 9 tiles: workgroup count not a multiple of the 8 XCDs
     (3, 1, 128, 64, "fp16"),      # H = 1, smallest N
+    (1, 2, 256, 256, "fp16"),     # d = 256 (the paper's third head dimension, Section 7): one wavefront per SIMD
+    (2, 1, 384, 256, "bf16"),
+    (1, 3, 640, 256, "fp16"),
 ])
 def test_parity_elementwise(B, H, N, d, dtype):
     seed = 1000 + 7 * N + d + B
@@ -105,6 +108,24 @@ def test_parity_outlier_keys_medium():
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), scale)
     o, lse = _run_gpu(qb, kb, vb, "fp16", scale)
     _check(o, lse, o_ref, lse_ref, "outliers N2048 d64")
+
+
+def test_parity_paper_shape_d256_sampled():
+    # the paper's d = 256 benchmark shape (Section 7: batch 4, N = 4096, 8 heads x 256), sampled rows
+    B, H, N, d = 4, 8, 4096, 256
+    print("paper shape d256", flush=True)
+    qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 256256)
+    scale = 1.0 / 16.0
+    o, lse = _run_gpu(qb, kb, vb, "fp16", scale)
+    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+    r = np.random.Generator(np.random.PCG64(31))
+    n = 512
+    rows = np.stack([r.integers(0, B, n), r.integers(0, H, n), r.integers(0, N, n)], axis=1).astype(np.int32)
+    rows[0], rows[1] = (0, 0, 0), (B - 1, H - 1, N - 1)
+    q, k, v = (oracle.widen(x, "fp16") for x in (qb, kb, vb))
+    o_rows, lse_rows = oracle.attention_rows(q, k, v, scale, rows)
+    _check(o[rows[:, 0], rows[:, 2], rows[:, 1], :], lse[rows[:, 0], rows[:, 1], rows[:, 2]], o_rows, lse_rows,
+           "paper shape B4 H8 N4096 d256 (512 sampled rows)")
 
 
 # ------------------------------------------------------------------ full-size workloads: sampled rows + whole heads
