@@ -36,8 +36,9 @@ enum {
   FA2_ERR_INVALID_ARG = -1, /* NULL Q/K/V/O; B, H, N or d <= 0; scale not finite or <= 0;
                                a pointer not 16-byte aligned (LSE: 4-byte); an unknown
                                variant or mask                                        */
-  FA2_ERR_UNSUPPORTED = -2, /* d not in {64, 128}; N not a multiple of 128; unknown dtype;
-                               a problem too large for 32-bit tile counts             */
+  FA2_ERR_UNSUPPORTED = -2, /* d not in {64, 128, 256}; unknown dtype; a problem too large
+                               for 32-bit tile counts and offsets; a tile shape or mask
+                               that cannot run the given sizes (see each entry point)  */
   FA2_ERR_LAUNCH = -3       /* the HIP runtime refused the launch                     */
 };
 
@@ -50,8 +51,9 @@ enum {
  *  O        out  device, same shape, layout and element type as Q.  Rounded once, from the fp32
  *                accumulator, to nearest-even.
  *  LSE      out  device, [B][H][N] contiguous fp32, natural logarithm; may be NULL (not written).
- *  B,H,N,d       batch, heads, sequence length, head dimension.  d must be 64 or 128 and N a
- *                multiple of 128.
+ *  B,H,N,d       batch, heads, sequence length, head dimension.  d must be 64, 128 or 256 (the head
+ *                dimensions of the paper's benchmarks, Section 7); N is any length >= 1 (a length
+ *                that is not a multiple of 128 runs a kernel variant that masks the partial tiles).
  *  scale         multiplies Q K^T before the softmax; callers pass 1/sqrt(d).  Must be finite
  *                and > 0 (the kernel takes the row maximum before scaling).
  *  dtype         FA2_FP16 or FA2_BF16.  Products are accumulated in fp32; P is rounded to `dtype`
@@ -73,9 +75,9 @@ enum {
   FA2_VARIANT_AUTO = 0,   /* pick by problem shape (what fa2_fwd does)                                  */
   FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (32 per wavefront), 2 workgroups per CU       */
   FA2_VARIANT_WIDE = 2,   /* 256 query rows per workgroup (4 wavefronts x 64 rows), 1 workgroup per CU;
-                             needs N to be a multiple of 256                                            */
+                             needs N to be a multiple of 256 and d <= 128                               */
   FA2_VARIANT_NARROW8 = 3 /* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
-                             K/V loaded three tiles ahead; needs N to be a multiple of 256              */
+                             K/V loaded three tiles ahead; needs N to be a multiple of 256 and d <= 128 */
 };
 
 /*
@@ -107,6 +109,23 @@ enum {
  */
 int fa2_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
                    float scale, int dtype, int mask, void* stream);
+
+/*
+ * fa2_fwd_qk -- the general shape of the Section 2 formula: Nq query rows attend to Nk keys and values
+ * (the paper's SEQLEN and KEYLEN of Section 3), any Nq >= 1 and Nk >= 1.
+ *
+ *  Q        in   device, [B][Nq][H][d];   K, V  in  device, [B][Nk][H][d];
+ *  O        out  device, [B][Nq][H][d];   LSE   out device, [B][H][Nq] fp32, may be NULL.
+ *  mask          FA2_MASK_NONE, or FA2_MASK_CAUSAL, which needs Nq == Nk (FA2_ERR_UNSUPPORTED otherwise).
+ *
+ * Partial tiles are handled inside the kernel: columns of S that belong to keys past Nk-1 are set to
+ * -inf before the softmax (exact zeros in P), rows past Nq-1 are never stored, and no byte outside the
+ * four tensors is read or written.  Everything else -- layout within a row, element types, scale,
+ * stream, ownership, error behaviour -- is as for fa2_fwd; fa2_fwd(…, N, …) is fa2_fwd_qk with
+ * Nq = Nk = N and FA2_MASK_NONE.
+ */
+int fa2_fwd_qk(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, int d,
+               float scale, int dtype, int mask, void* stream);
 
 /* Static, NUL-terminated description of a return code (never NULL). */
 const char* fa2_strerror(int code);

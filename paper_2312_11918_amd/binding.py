@@ -52,6 +52,8 @@ def load_library():
         lib.fa2_fwd_variant.restype = ci
         lib.fa2_fwd_masked.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, ci, vp]
         lib.fa2_fwd_masked.restype = ci
+        lib.fa2_fwd_qk.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, ci, ci, vp]
+        lib.fa2_fwd_qk.restype = ci
         lib.fa2_strerror.argtypes = [ci]
         lib.fa2_strerror.restype = ctypes.c_char_p
         lib.fa2_version.argtypes = []
@@ -86,11 +88,18 @@ def fa2_fwd_masked_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, N, d, scale, d
                                              float(scale), int(dtype), int(mask), stream))
 
 
+def fa2_fwd_qk_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Nq, Nk, d, scale, dtype, mask, stream=None) -> int:
+    """Call ``fa2_fwd_qk`` (Nq queries, Nk keys, optional causal mask) with raw device addresses; returns the C code."""
+    return int(load_library().fa2_fwd_qk(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, int(B), int(H), int(Nq), int(Nk), int(d),
+                                         float(scale), int(dtype), int(mask), stream))
+
+
 def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, stream=None,
             variant: int = FA2_VARIANT_AUTO, causal: bool = False):
-    """Attention forward on torch CUDA tensors ``[B, N, H, d]`` (fp16 or bf16, contiguous).
+    """Attention forward on torch CUDA tensors: ``q`` ``[B, Nq, H, d]``, ``k`` and ``v`` ``[B, Nk, H, d]`` (fp16 or
+    bf16, contiguous).
 
-    Returns ``(O, LSE)`` with O like ``q`` and LSE ``[B, H, N]`` fp32 (``None`` if ``return_lse`` is
+    Returns ``(O, LSE)`` with O like ``q`` and LSE ``[B, H, Nq]`` fp32 (``None`` if ``return_lse`` is
     false).  The kernel is enqueued on ``stream`` (a ``torch.cuda.Stream``) or on torch's current stream.
     ``variant`` selects the tile shape (``FA2_VARIANT_*``); the default lets the library choose.
     ``causal`` masks S so that query i sees keys j <= i only (``fa2_fwd_masked``; default tile shape only).
@@ -107,11 +116,13 @@ def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, 
         raise ValueError(f"unsupported element type {q.dtype}")
     if k.dtype != q.dtype or v.dtype != q.dtype:
         raise ValueError("q, k, v must share one element type")
-    if q.dim() != 4 or k.shape != q.shape or v.shape != q.shape:
-        raise ValueError(f"q, k, v must all be [B, N, H, d]; got {tuple(q.shape)}, {tuple(k.shape)}, {tuple(v.shape)}")
+    if (q.dim() != 4 or k.dim() != 4 or v.shape != k.shape or k.shape[0] != q.shape[0] or k.shape[2:] != q.shape[2:]):
+        raise ValueError(f"q must be [B, Nq, H, d], k and v [B, Nk, H, d]; got {tuple(q.shape)}, {tuple(k.shape)}, "
+                         f"{tuple(v.shape)}")
     if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
         raise ValueError("q, k, v must be contiguous")
     B, N, H, d = q.shape
+    Nk = k.shape[1]
     if out is None:
         out = torch.empty_like(q)
     elif out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
@@ -126,12 +137,17 @@ def fa2_fwd(q, k, v, scale: float, out=None, lse=None, return_lse: bool = True, 
     with torch.cuda.device(q.device):
         s = stream if stream is not None else torch.cuda.current_stream()
         ptrs = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), None if lse is None else lse.data_ptr())
-        if causal:
-            if variant != FA2_VARIANT_AUTO:
-                raise ValueError("the causal mask runs on the library's default tile shape only")
+        if variant != FA2_VARIANT_AUTO:
+            if causal or Nk != N:
+                raise ValueError("an explicit tile shape runs square, unmasked problems only")
+            rc = fa2_fwd_variant_raw(*ptrs, B, H, N, d, scale, dtype, variant, s.cuda_stream)
+        elif Nk != N:
+            rc = fa2_fwd_qk_raw(*ptrs, B, H, N, Nk, d, scale, dtype, FA2_MASK_CAUSAL if causal else FA2_MASK_NONE,
+                                s.cuda_stream)
+        elif causal:
             rc = fa2_fwd_masked_raw(*ptrs, B, H, N, d, scale, dtype, FA2_MASK_CAUSAL, s.cuda_stream)
         else:
-            rc = fa2_fwd_variant_raw(*ptrs, B, H, N, d, scale, dtype, variant, s.cuda_stream)
+            rc = fa2_fwd_raw(*ptrs, B, H, N, d, scale, dtype, s.cuda_stream)
     if rc != FA2_OK:
         raise Fa2Error(rc, fa2_strerror(rc))
     return out, lse

@@ -145,14 +145,16 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 // softmax; here those with key index > query index).  A Q tile then stops at its diagonal: it visits
 // (qt+1)*kNBuf K/V tiles instead of N/kBc, only the last kNBuf of them straddle the diagonal and need the
 // element-wise mask, and Q tiles are dealt heaviest first.
-template <int DT, int D, int kWv, int kNBuf, bool kCausal>
-__global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_fwd_kernel(const uint16_t* __restrict__ Q,
-                                                                             const uint16_t* __restrict__ K,
-                                                                             const uint16_t* __restrict__ V,
-                                                                             uint16_t* __restrict__ O,
-                                                                             float* __restrict__ LSE, int H, int N,
-                                                                             float scale_log2e, int n_qtiles,
-                                                                             int total_tiles) {
+//
+// kRagged lifts the restriction to whole tiles: Nq query rows and Nk keys of any size >= 1.  Query rows past
+// Nq-1 are computed from a copy of the last row and not stored; K/V rows past Nk-1 are staged as copies of
+// the last row (finite data) and their columns of S are set to -inf in the last kNBuf tiles, the only ones
+// that can hold them; the tile count is rounded up to a multiple of kNBuf (a padding tile is fully masked).
+template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
+__global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_fwd_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    uint16_t* __restrict__ O, float* __restrict__ LSE, int H, int Nq, int Nk, float scale_log2e, int n_qtiles,
+    int total_tiles) {
   using E = Elem<DT>;
   using T = Tile<D>;
   using std::false_type;
@@ -208,7 +210,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   int qt, q_row, n_tiles;  // set per pass
 
   const size_t row_stride = (size_t)H * D;                          // elements between consecutive tokens
-  const size_t head_base = ((size_t)b * N * H + (size_t)h) * D;     // element (b, 0, h, 0)
+  const size_t head_base = ((size_t)b * Nq * H + (size_t)h) * D;    // element (b, 0, h, 0) of Q and O
+  const size_t kv_head_base = ((size_t)b * Nk * H + (size_t)h) * D; // element (b, 0, h, 0) of K and V
   const size_t tile_stride = (size_t)kBc * row_stride;              // elements between consecutive K/V tiles
 
   // Q_i fragment, held in registers for the whole loop: B operand of S^T = K Q^T.
@@ -220,16 +223,31 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Buffer descriptors (base, byte range) of this head's K and V rows: a raw buffer load takes a scalar
   // descriptor, a scalar tile offset and the 32-bit per-lane offset, and its range check turns any
   // offset past the last row into zeros instead of a fault.
-  const uint32_t head_bytes = (uint32_t)(((size_t)(N - 1) * row_stride + D) * 2);
+  const uint32_t head_bytes = (uint32_t)(((size_t)(Nk - 1) * row_stride + D) * 2);
   const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(K + head_base), 0, (int)head_bytes, kBufferFlags);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(K + kv_head_base), 0, (int)head_bytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(V + head_base), 0, (int)head_bytes, kBufferFlags);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(V + kv_head_base), 0, (int)head_bytes, kBufferFlags);
   const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
   const uint32_t row_bytes = (uint32_t)(row_stride * 2);
   // is_k is a compile-time tag: K and V tiles use different chunk swizzles.  The per-lane source offsets are
   // recomputed at every call (a few integer operations per tile) instead of being kept in registers.
   auto stage_in = [&](auto is_k, __amdgpu_buffer_rsrc_t rsrc, int j, uint16_t* lds_tile) __attribute__((always_inline)) {
+    if (kRagged && (j + 1) * kBc > Nk) {
+      // a tile with rows past the last key: those rows are filled with copies of the last key's row, so LDS
+      // holds finite numbers everywhere (their columns of S are masked; 0 * finite = 0 in GEMM-II)
+#pragma unroll
+      for (int i = 0; i < kLoadsPerWave; ++i) {
+        const int chunk = 64 * (wave * kLoadsPerWave + i) + lane;
+        const int row = chunk / T::kChunksPerRow, pos = chunk % T::kChunksPerRow;
+        const int swz = decltype(is_k)::value ? T::swz_k(row) : T::swz_v(row);
+        const int row_g = min(j * kBc + row, Nk - 1);
+        const uint32_t src = (uint32_t)row_g * row_bytes + 16u * (uint32_t)(pos ^ swz);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(lds_tile + 512 * (wave * kLoadsPerWave + i)), 16,
+                                                 (int)src, 0, 0, 0);
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int chunk = 64 * (wave * kLoadsPerWave + i) + lane;
@@ -430,10 +448,11 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     if (pass > 0) __syncthreads();  // the first Q tile's last K/V reads are over before the buffers are refilled
     qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
     q_row = qt * kRows + wave * 32 + r;
-    // a multiple of kNBuf either way (N is a multiple of 32*kWv); causal: the keys up to the end of this Q tile
-    n_tiles = kCausal ? (qt + 1) * kNBuf : N / kBc;
+    // a multiple of kNBuf in every case; causal: the keys up to the end of this Q tile
+    n_tiles = kCausal ? (qt + 1) * kNBuf : kRagged ? (Nk + kNBuf * kBc - 1) / (kNBuf * kBc) * kNBuf : Nk / kBc;
     {
-      const uint16_t* qp = Q + head_base + (size_t)q_row * row_stride + 8 * hh;
+      const int q_row_ld = kRagged ? min(q_row, Nq - 1) : q_row;
+      const uint16_t* qp = Q + head_base + (size_t)q_row_ld * row_stride + 8 * hh;
 #pragma unroll
       for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
     }
@@ -467,10 +486,16 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     }
     // last kNBuf tiles: wait for everything, and the very last tile has no successor.  Under the causal mask
     // these are exactly the tiles of this Q tile's own rows, the ones the diagonal crosses.
-    using mask_tail = std::integral_constant<bool, kCausal>;
+    // Without the causal mask the same tiles are the only ones that can hold keys past Nk-1.
+    using mask_tail = std::integral_constant<bool, kCausal || kRagged>;
     static_for<kNBuf>([&](auto t) {
       constexpr int i = decltype(t)::value;
-      const int visible = wave * 32 + r - 4 * hh - i * kBc;  // (q_row - first key of tile j+i) - 4 hh
+      // causal: (q_row - first key of tile j+i) - 4 hh; a stored row (q_row < Nq = Nk) never sees a key past
+      // Nk-1 through it.  Otherwise: (last key - first key of tile j+i) - 4 hh.
+      int visible = kCausal ? wave * 32 + r - 4 * hh - i * kBc : Nk - 1 - (j + i) * kBc - 4 * hh;
+      // computed here, not hoisted above the main loop where 32 comparison results per tile would sit in
+      // scalar registers for the whole loop
+      if constexpr (mask_tail::value) asm volatile("" : "+v"(visible));
       if constexpr (i + 1 < kNBuf) {
         iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
         boundary(false_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
@@ -482,19 +507,21 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
     const float l_tot = sum_with_partner_half(l_run);
     const float inv_l = 1.0f / l_tot;
-    uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
+    if (!kRagged || q_row < Nq) {
+      uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
 #pragma unroll
-    for (int db = 0; db < kDBlocks; ++db) {
+      for (int db = 0; db < kDBlocks; ++db) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        // accumulator registers 4g..4g+3 hold d = 32 db + 8 g + 4 hh + (0..3) of this lane's query
-        u32x2 w = {E::pack2(ot[db][4 * g + 0] * inv_l, ot[db][4 * g + 1] * inv_l),
-                   E::pack2(ot[db][4 * g + 2] * inv_l, ot[db][4 * g + 3] * inv_l)};
-        *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
+        for (int g = 0; g < 4; ++g) {
+          // accumulator registers 4g..4g+3 hold d = 32 db + 8 g + 4 hh + (0..3) of this lane's query
+          u32x2 w = {E::pack2(ot[db][4 * g + 0] * inv_l, ot[db][4 * g + 1] * inv_l),
+                     E::pack2(ot[db][4 * g + 2] * inv_l, ot[db][4 * g + 3] * inv_l)};
+          *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
+        }
       }
-    }
-    if (LSE != nullptr && hh == 0) {
-      LSE[((size_t)b * H + h) * N + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
+      if (LSE != nullptr && hh == 0) {
+        LSE[((size_t)b * H + h) * Nq + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
+      }
     }
   }  // pass
 }
@@ -851,55 +878,59 @@ __global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_
   }
 }
 
+// One instantiation of the 32-row kernel.
+template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
+void launch_rows32(const void* Q, const void* K, const void* V, void* O, float* LSE, int H, int Nq, int Nk,
+                   float scale_log2e, int n_qtiles, int total, hipStream_t stream) {
+  hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged>), dim3((unsigned)total), dim3(kWv * 64), 0,
+                     stream, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                     static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles,
+                     total);
+}
+
 template <int DT, int D>
-int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, float scale,
+int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, float scale,
            int variant, int mask, hipStream_t stream) {
   const float scale_log2e = scale * 1.44269504088896340736f;
-  const bool wide = variant == FA2_VARIANT_WIDE;
   const bool rows256 = variant == FA2_VARIANT_WIDE || variant == FA2_VARIANT_NARROW8;
-  const int n_qtiles = N / (rows256 ? kWideBr : kBr);
+  const bool causal = mask == FA2_MASK_CAUSAL;
+  const bool ragged = Nq % kBr != 0 || Nk % kBr != 0;  // 128-row shape only (checked by the caller)
+  const int rows = rows256 ? kWideBr : kBr;
+  const int n_qtiles = (Nq + rows - 1) / rows;
   // causal: one workgroup per pair of Q tiles (n_qtiles-1-p, p)
-  const long long total = (long long)B * H * (mask == FA2_MASK_CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles);
-  if (total > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
-  if (mask == FA2_MASK_CAUSAL) {  // 128-row shape only (checked by the caller)
-    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, true>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
-                       n_qtiles, (int)total);
-  } else if constexpr (D == 256) {  // one tile shape at this head dimension (checked by the caller)
-    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, false>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
-                       n_qtiles, (int)total);
-  } else if (wide) {
-    hipLaunchKernelGGL((fa2_fwd_wide_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
-                       n_qtiles, (int)total);
-  } else if (variant == FA2_VARIANT_NARROW8) {
-    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 8, 4, false>), dim3((unsigned)total), dim3(512), 0, stream,
-                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
-                       n_qtiles, (int)total);
+  const long long total_ll = (long long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);
+  if (total_ll > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
+  const int total = (int)total_ll;
+  if (rows256) {  // exact tiles, no mask, d <= 128 (checked by the caller)
+    if constexpr (D <= 128) {
+      if (variant == FA2_VARIANT_WIDE) {
+        hipLaunchKernelGGL((fa2_fwd_wide_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
+                           static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                           static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, Nq, scale_log2e,
+                           n_qtiles, total);
+      } else {
+        launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+      }
+    } else {
+      return FA2_ERR_UNSUPPORTED;
+    }
+  } else if (causal) {
+    if (ragged) launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+    else launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
   } else {
-    hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, 4, 2, false>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                       static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                       static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, N, scale_log2e,
-                       n_qtiles, (int)total);
+    if (ragged) launch_rows32<DT, D, 4, 2, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+    else launch_rows32<DT, D, 4, 2, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
   }
   return hipGetLastError() == hipSuccess ? FA2_OK : FA2_ERR_LAUNCH;
 }
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-}  // namespace
-
-namespace {
-int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d, float scale,
-        int dtype, int variant, int mask, void* stream) {
+int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, int d,
+        float scale, int dtype, int variant, int mask, void* stream) {
   // All validation happens before the first HIP call: an error launches nothing.
   if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return FA2_ERR_INVALID_ARG;
-  if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return FA2_ERR_INVALID_ARG;
+  if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || d <= 0) return FA2_ERR_INVALID_ARG;
   if (!(scale > 0.0f) || !(scale <= 3.0e38f)) return FA2_ERR_INVALID_ARG;  // rejects NaN, inf, <= 0
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(LSE, 4))
     return FA2_ERR_INVALID_ARG;
@@ -909,54 +940,63 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if (mask != FA2_MASK_NONE && mask != FA2_MASK_CAUSAL) return FA2_ERR_INVALID_ARG;
   if (dtype != FA2_FP16 && dtype != FA2_BF16) return FA2_ERR_UNSUPPORTED;
   if (d != 64 && d != 128 && d != 256) return FA2_ERR_UNSUPPORTED;
-  if (N % kBr != 0) return FA2_ERR_UNSUPPORTED;
-  if ((variant == FA2_VARIANT_WIDE || variant == FA2_VARIANT_NARROW8) && N % kWideBr != 0) return FA2_ERR_UNSUPPORTED;
+  if (mask == FA2_MASK_CAUSAL && Nq != Nk) return FA2_ERR_UNSUPPORTED;  // the diagonal is defined for a square S only
   // element offsets are computed in 64 bits; the row index b*N+n must still fit the tile arithmetic
-  if ((long long)B * N > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
+  const int n_max = Nq > Nk ? Nq : Nk;
+  if ((long long)B * n_max > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
   // the K/V rows of one batch entry are addressed with 32-bit byte offsets from a buffer descriptor
-  if ((unsigned long long)N * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32)) return FA2_ERR_UNSUPPORTED;
+  if ((unsigned long long)n_max * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32))
+    return FA2_ERR_UNSUPPORTED;
   if (variant == FA2_VARIANT_AUTO) {
     // Measured on MI355X with N(0,1) inputs, the 4-wavefront, 128-row shape is the fastest of the three on
     // every workload shape tried (N = 512 .. 16384, d = 64 and 128); the others stay selectable for sweeps.
     variant = FA2_VARIANT_NARROW;
   }
-  if (mask == FA2_MASK_CAUSAL && variant != FA2_VARIANT_NARROW) return FA2_ERR_UNSUPPORTED;
-  if (d == 256 && variant != FA2_VARIANT_NARROW) return FA2_ERR_UNSUPPORTED;
+  if (variant != FA2_VARIANT_NARROW) {
+    // the 256-row shapes exist for tile-shape sweeps: whole tiles, square, unmasked, d <= 128
+    if (Nq != Nk || Nq % kWideBr != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
-    return d == 64    ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
-           : d == 128 ? launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
-                      : launch<FA2_FP16, 256>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
+    return d == 64    ? launch<FA2_FP16, 64>(Q, K, V, O, LSE, B, H, Nq, Nk, scale, variant, mask, s)
+           : d == 128 ? launch<FA2_FP16, 128>(Q, K, V, O, LSE, B, H, Nq, Nk, scale, variant, mask, s)
+                      : launch<FA2_FP16, 256>(Q, K, V, O, LSE, B, H, Nq, Nk, scale, variant, mask, s);
   }
-  return d == 64    ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
-         : d == 128 ? launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s)
-                    : launch<FA2_BF16, 256>(Q, K, V, O, LSE, B, H, N, scale, variant, mask, s);
+  return d == 64    ? launch<FA2_BF16, 64>(Q, K, V, O, LSE, B, H, Nq, Nk, scale, variant, mask, s)
+         : d == 128 ? launch<FA2_BF16, 128>(Q, K, V, O, LSE, B, H, Nq, Nk, scale, variant, mask, s)
+                    : launch<FA2_BF16, 256>(Q, K, V, O, LSE, B, H, Nq, Nk, scale, variant, mask, s);
 }
+
 }  // namespace
 
 extern "C" int fa2_fwd_variant(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N,
                                int d, float scale, int dtype, int variant, void* stream) {
-  return run(Q, K, V, O, LSE, B, H, N, d, scale, dtype, variant, FA2_MASK_NONE, stream);
+  return run(Q, K, V, O, LSE, B, H, N, N, d, scale, dtype, variant, FA2_MASK_NONE, stream);
 }
 
 extern "C" int fa2_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N,
                               int d, float scale, int dtype, int mask, void* stream) {
-  return run(Q, K, V, O, LSE, B, H, N, d, scale, dtype, FA2_VARIANT_AUTO, mask, stream);
+  return run(Q, K, V, O, LSE, B, H, N, N, d, scale, dtype, FA2_VARIANT_AUTO, mask, stream);
+}
+
+extern "C" int fa2_fwd_qk(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq,
+                          int Nk, int d, float scale, int dtype, int mask, void* stream) {
+  return run(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, dtype, FA2_VARIANT_AUTO, mask, stream);
 }
 
 extern "C" int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
                        float scale, int dtype, void* stream) {
-  return run(Q, K, V, O, LSE, B, H, N, d, scale, dtype, FA2_VARIANT_AUTO, FA2_MASK_NONE, stream);
+  return run(Q, K, V, O, LSE, B, H, N, N, d, scale, dtype, FA2_VARIANT_AUTO, FA2_MASK_NONE, stream);
 }
 
 extern "C" const char* fa2_strerror(int code) {
   switch (code) {
     case FA2_OK: return "success";
     case FA2_ERR_INVALID_ARG: return "invalid argument (NULL or misaligned pointer, non-positive size, scale not finite and > 0, or unknown variant or mask)";
-    case FA2_ERR_UNSUPPORTED: return "unsupported problem (d must be 64 or 128, N a multiple of 128, dtype fp16 or bf16)";
+    case FA2_ERR_UNSUPPORTED: return "unsupported problem (d must be 64, 128 or 256; dtype fp16 or bf16; the causal mask needs Nq == Nk; the 256-row tile shapes need d <= 128 and N a multiple of 256; sizes must fit 32-bit offsets)";
     case FA2_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     default: return "unknown fa2 error code";
   }
 }
 
-extern "C" int fa2_version(void) { return 200; /* 0.2.0 */ }
+extern "C" int fa2_version(void) { return 300; /* 0.3.0 */ }

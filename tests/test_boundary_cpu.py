@@ -18,7 +18,7 @@ def _declared_functions():
 
 
 def test_header_declares_the_boundary():
-    assert {"fa2_fwd", "fa2_fwd_variant", "fa2_fwd_masked", "fa2_strerror", "fa2_version"} <= set(_declared_functions())
+    assert {"fa2_fwd", "fa2_fwd_variant", "fa2_fwd_masked", "fa2_fwd_qk", "fa2_strerror", "fa2_version"} <= set(_declared_functions())
 
 
 def test_library_exports_every_declared_symbol():
@@ -54,8 +54,8 @@ P = 0x1000  # a 16-byte aligned, never dereferenced "device address": validation
     (dict(lse=P + 2), fa2.FA2_ERR_INVALID_ARG),
     (dict(d=96), fa2.FA2_ERR_UNSUPPORTED),
     (dict(d=512), fa2.FA2_ERR_UNSUPPORTED),
-    (dict(N=100), fa2.FA2_ERR_UNSUPPORTED),
-    (dict(N=64), fa2.FA2_ERR_UNSUPPORTED),
+    (dict(N=-128), fa2.FA2_ERR_INVALID_ARG),
+    (dict(H=1 << 15, N=1 << 16, d=128), fa2.FA2_ERR_UNSUPPORTED),      # a head's rows span >= 4 GiB: 32-bit offsets
     (dict(dtype=7), fa2.FA2_ERR_UNSUPPORTED),
     (dict(B=1 << 20, N=1 << 20), fa2.FA2_ERR_UNSUPPORTED),
 ])
@@ -91,7 +91,6 @@ def test_variant_entry_rejects_bad_arguments_without_a_launch(variant, args, cod
     (2, {}, fa2.FA2_ERR_INVALID_ARG),                                  # unknown mask
     (-1, {}, fa2.FA2_ERR_INVALID_ARG),
     (fa2.FA2_MASK_CAUSAL, dict(k=None), fa2.FA2_ERR_INVALID_ARG),
-    (fa2.FA2_MASK_CAUSAL, dict(N=192), fa2.FA2_ERR_UNSUPPORTED),
     (fa2.FA2_MASK_CAUSAL, dict(d=96), fa2.FA2_ERR_UNSUPPORTED),
     (fa2.FA2_MASK_CAUSAL, dict(scale=-1.0), fa2.FA2_ERR_INVALID_ARG),
     (fa2.FA2_MASK_NONE, dict(dtype=3), fa2.FA2_ERR_UNSUPPORTED),
@@ -101,6 +100,25 @@ def test_masked_entry_rejects_bad_arguments_without_a_launch(mask, args, code):
     a.update(args)
     rc = fa2.fa2_fwd_masked_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["N"], a["d"], a["scale"],
                                 a["dtype"], mask)
+    assert rc == code
+
+
+@pytest.mark.parametrize("Nq,Nk,mask,args,code", [
+    (0, 128, fa2.FA2_MASK_NONE, {}, fa2.FA2_ERR_INVALID_ARG),
+    (128, 0, fa2.FA2_MASK_NONE, {}, fa2.FA2_ERR_INVALID_ARG),
+    (128, -5, fa2.FA2_MASK_NONE, {}, fa2.FA2_ERR_INVALID_ARG),
+    (100, 100, 7, {}, fa2.FA2_ERR_INVALID_ARG),
+    (100, 101, fa2.FA2_MASK_CAUSAL, {}, fa2.FA2_ERR_UNSUPPORTED),      # the causal diagonal needs a square S
+    (100, 300, fa2.FA2_MASK_NONE, dict(d=80), fa2.FA2_ERR_UNSUPPORTED),
+    (100, 300, fa2.FA2_MASK_NONE, dict(v=None), fa2.FA2_ERR_INVALID_ARG),
+    (100, 300, fa2.FA2_MASK_NONE, dict(lse=P + 1), fa2.FA2_ERR_INVALID_ARG),
+    (1 << 20, 16, fa2.FA2_MASK_NONE, dict(B=1 << 12), fa2.FA2_ERR_UNSUPPORTED),
+])
+def test_qk_entry_rejects_bad_arguments_without_a_launch(Nq, Nk, mask, args, code):
+    a = dict(_OKARGS)
+    a.update(args)
+    rc = fa2.fa2_fwd_qk_raw(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], Nq, Nk, a["d"], a["scale"],
+                            a["dtype"], mask)
     assert rc == code
 
 
