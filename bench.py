@@ -34,11 +34,33 @@ HEADLINE = 3
 MEASURED_TRAFFIC_BYTES = {"B8_H16_N2048_d128_fp16": int((98402.31 * 2.0 + 66560.00) * 1024)}
 
 
-def _device_tensors(index):
-    import torch
+_CUSTOM = {}
+
+
+def _custom_workload(spec):
+    """Registers a workload `B,H,N,d,dtype` (e.g. 4,8,4096,256,fp16) under index 0, same input recipe as the five."""
     from paper_2312_11918_amd import workloads
 
-    w, qb, kb, vb = workloads.make_workload(index)
+    B, H, N, d, dtype = spec.split(",")
+    B, H, N, d = int(B), int(H), int(N), int(d)
+    # index 100 + ... only feeds the seed (SEED_BASE + index); it is not one of the numbered workloads
+    _CUSTOM[0] = workloads.Workload(100 + (N + d) % 1000, f"B{B}_H{H}_N{N}_d{d}_{dtype}", B, H, N, d, dtype)
+    return 0
+
+
+def _make(index):
+    from paper_2312_11918_amd import workloads
+
+    if index in _CUSTOM:
+        w = _CUSTOM[index]
+        return (w,) + tuple(workloads.make_qkv(w.B, w.N, w.H, w.d, w.dtype, w.seed))
+    return workloads.make_workload(index)
+
+
+def _device_tensors(index):
+    import torch
+
+    w, qb, kb, vb = _make(index)
     tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
     q, k, v = (torch.from_numpy(x.view(np.int16)).cuda().view(tdt) for x in (qb, kb, vb))
     return w, q, k, v
@@ -74,9 +96,8 @@ def _time_workload(index, steps, warmup, causal=False):
 def _cpu_baseline(index, target_seconds=15.0):
     """The fp64 oracle, as it stands, on this host's cores, on the first batch entries of the workload."""
     import oracle
-    from paper_2312_11918_amd import workloads
 
-    w, qb, kb, vb = workloads.make_workload(index)
+    w, qb, kb, vb = _make(index)
     # calibration on one head, then as many whole batch entries as fit the time target
     sl = (slice(0, 1), slice(None), slice(0, 1))
     q1, k1, v1 = (oracle.widen(x[sl], w.dtype) for x in (qb, kb, vb))
@@ -100,6 +121,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=HEADLINE, help="headline workload index (1..5)")
+    ap.add_argument("--shape", default=None, metavar="B,H,N,d,dtype",
+                    help="time this shape instead of a numbered workload (same seeded N(0,1) recipe), e.g. "
+                         "4,8,4096,256,fp16; implies --only-headline")
+    ap.add_argument("--causal", action="store_true",
+                    help="time fa2_fwd_masked with the causal mask; FLOPs are then counted as 2*B*H*N^2*d")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--only-headline", action="store_true", help="do not time the other workloads")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="K",
@@ -119,6 +145,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
     fa2.load_library()   # fail loudly if the extension is not built
+    if args.shape:
+        args.workload = _custom_workload(args.shape)
+        args.only_headline = True
 
     if args.copy_calibration > 0:
         wc, qc, _, _ = _device_tensors(args.workload)
@@ -130,8 +159,9 @@ def main():
               f"(reads {qc.numel() * 2} B, writes {qc.numel() * 2} B each)", file=sys.stderr)
         del qc, dst
 
-    w, ms, wall_ms = _time_workload(args.workload, args.steps, args.warmup)
-    tflops = w.flops / (ms * 1e-3) / 1e12
+    w, ms, wall_ms = _time_workload(args.workload, args.steps, args.warmup, causal=args.causal)
+    flops = w.flops * (0.5 if args.causal else 1.0)
+    tflops = flops / (ms * 1e-3) / 1e12
     alg_bytes = 4 * w.B * w.H * w.N * w.d * 2 + 4 * w.B * w.H * w.N
 
     per_workload = {}
@@ -159,7 +189,7 @@ def main():
                   "flops_counted": "2*B*H*N^2*d"}
 
     out = {
-        "metric": "attention fwd TFLOP/s (4*B*H*N^2*d)",
+        "metric": "attention fwd TFLOP/s (2*B*H*N^2*d, causal)" if args.causal else "attention fwd TFLOP/s (4*B*H*N^2*d)",
         "value": round(tflops, 2),
         "unit": "TFLOP/s",
         "n_gpus": 1,
@@ -172,12 +202,12 @@ def main():
         "vs_baseline": None,
         "dtype": "fp16" if w.dtype == "fp16" else "bf16",
         "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": False,
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": bool(args.causal),
                    "scale": "1/sqrt(d)", "inputs": "i.i.d. N(0,1), seeded, resident in HBM"},
         "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "algorithmic_flops_per_launch": w.flops, "algorithmic_hbm_bytes_per_launch": alg_bytes,
+                     "traffic": None if args.causal else MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "algorithmic_flops_per_launch": flops, "algorithmic_hbm_bytes_per_launch": alg_bytes,
                      "kernel": "fa2_fwd_kernel", "kernel_ms": round(ms, 5)},
         "workloads": per_workload,
         "causal_same_shape": causal,

@@ -76,8 +76,11 @@ enum {
   FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (32 per wavefront), 2 workgroups per CU       */
   FA2_VARIANT_WIDE = 2,   /* 256 query rows per workgroup (4 wavefronts x 64 rows), 1 workgroup per CU;
                              needs N to be a multiple of 256 and d <= 128                               */
-  FA2_VARIANT_NARROW8 = 3 /* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
+  FA2_VARIANT_NARROW8 = 3,/* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
                              K/V loaded three tiles ahead; needs N to be a multiple of 256 and d <= 128 */
+  FA2_VARIANT_PIPE = 4    /* the NARROW shape with the softmax of 32 keys interleaved, instruction by
+                             instruction, with the MFMAs of the neighbouring 32-key stages; needs N to
+                             be a multiple of 128 and d <= 128                                          */
 };
 
 /*

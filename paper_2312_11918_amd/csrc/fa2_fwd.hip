@@ -150,7 +150,13 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 // Nq-1 are computed from a copy of the last row and not stored; K/V rows past Nk-1 are staged as copies of
 // the last row (finite data) and their columns of S are set to -inf in the last kNBuf tiles, the only ones
 // that can hold them; the tile count is rounded up to a multiple of kNBuf (a padding tile is fully masked).
-template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
+//
+// kPipe selects a software pipeline inside the wavefront, over STAGES of 32 keys (half a K/V tile):
+//     stage s:   matrix cores:  O += P~_{s-1} V_{s-1}   and   S_{s+1} = K_{s+1} Q^T, MFMAs alternating
+//                vector ALU:    online softmax of S_s -> P~_s, cut into chunks that follow the MFMAs one by one
+// so that every wavefront offers work for both pipes all the time, instead of a block of softmax followed by a
+// block of MFMAs that has to meet the opposite block of the other wavefront on its SIMD.
+template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged, bool kPipe = false>
 __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_fwd_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ LSE, int H, int Nq, int Nk, float scale_log2e, int n_qtiles,
@@ -162,6 +168,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   static_assert(kNBuf == 2 || kNBuf == 4, "two or four LDS buffers per operand");
   constexpr int kRows = 32 * kWv;   // query rows per workgroup
   static_assert(kRows == kNBuf * kBc, "a Q tile spans exactly kNBuf K/V tiles (the causal tile count relies on it)");
+  static_assert(!kPipe || kNBuf == 2, "the stage pipeline is written for two LDS buffers per operand");
   constexpr int kKSteps = D / 16;   // MFMA steps along d for S^T = K Q^T
   constexpr int kDBlocks = D / 32;  // 32-row blocks of O^T
   constexpr int kKBlocks = kBc / 32;  // 32-key blocks of S^T
@@ -277,7 +284,10 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Accumulators of Algorithm 2: O^T (fp32), the rowmax reference and the running rowsum.  Each half
   // of the wavefront keeps the partial rowsum of its own keys; the two are added in the epilogue.
   f32x16 ot[kDBlocks];
-  f32x16 st[kKBlocks];  // S^T of the tile being processed
+  f32x16 st[kKBlocks];  // S^T of the tile being processed; stage pipeline: st[s % 2] is S^T of stage s
+  u32x4 pbuf[2][2];          // stage pipeline only: P~ of stages s-1 and s (two 16-key MFMA steps each)
+  float alpha_pend = 1.f;    // stage pipeline only: rescale of O decided by the last softmax, not yet applied
+  bool rescale_pend = false;
   float m_ref;          // reference point of the exponentials, in units of the unscaled logits q.k
   float mc_ref;         // m_ref * scale * log2(e)
   float l_run;
@@ -421,6 +431,133 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     }
   };
 
+  // ---- stage pipeline (kPipe) ----
+  // One stage, kPar = s % 2 (also the half of the K/V tile its 32 keys are in).
+  //   kG2: O += P~_{s-1} V_{s-1}; v_half points at the 32 rows of V of stage s-1; P~ is pbuf[kPar ^ 1].
+  //   kG1: S_{s+1} = K_{s+1} Q^T into st[kPar ^ 1]; k_half points at the 32 rows of K of stage s+1.
+  //   kSm: softmax of st[kPar] into pbuf[kPar].  mask_on (uniform): the stage may hold masked keys; then
+  //        register v of S^T is masked when 8 (v/4) + v%4 > visible.
+  // The rescale of O that the softmax of stage s-1 decided is applied first: O then refers to the same
+  // reference point as P~_{s-1}.
+  auto stage = [&](auto g2_tag, auto g1_tag, auto sm_tag, auto par_tag, bool mask_on, int visible, const uint16_t* v_half,
+                   const uint16_t* k_half) __attribute__((always_inline)) {
+    constexpr bool kG2 = decltype(g2_tag)::value, kG1 = decltype(g1_tag)::value, kSm = decltype(sm_tag)::value;
+    constexpr int kPar = decltype(par_tag)::value;
+    constexpr int kN2 = 2 * kDBlocks, kN1 = kKSteps;   // MFMAs of the two products per stage (equal)
+    static_assert(kN1 == kN2, "the two products of a stage have the same number of MFMAs");
+    constexpr int kFull = kN1 + kN2;                   // MFMA slots of a complete stage
+    constexpr int kSlots = (kG2 ? kN2 : 0) + (kG1 ? kN1 : 0);
+    constexpr int kMaxSlots = kFull >= 16 ? 2 : 1;     // slots that hold the row maximum (8 pairs)
+    constexpr int kExpFirst = kMaxSlots + 2;           // then two slots for the reference point
+    constexpr int kExpSlots = kFull - kExpFirst;
+
+    if constexpr (kSm && (kCausal || kRagged)) {
+      if (mask_on) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (8 * (v / 4) + (v % 4) > visible) st[kPar][v] = -INFINITY;
+      }
+    }
+    if (kG2 && rescale_pend) {  // rare: the reference point moved in the previous softmax
+#pragma unroll
+      for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ot[db][v] *= alpha_pend;
+    }
+
+    // MFMA step i of the stage: with both products, even steps belong to GEMM-II and odd steps to GEMM-I
+    auto frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
+      const bool second = (kG2 && kG1) ? (i & 1) == 0 : kG2;
+      const int idx = (kG2 && kG1) ? i / 2 : i;
+      if (second) {
+        const int t = idx / kDBlocks, db = idx % kDBlocks;
+        const uint16_t* p = v_half + v_addr[db] + t * 16 * D;
+        const u32x2 lo = lds_read_tr16(p);
+        const u32x2 hi = lds_read_tr16(p + 8 * D);
+        return u32x4{lo[0], lo[1], hi[0], hi[1]};
+      }
+      return *reinterpret_cast<const u32x4*>(k_half + k_addr[idx]);
+    };
+    u32x4 ring[kRing];
+#pragma unroll
+    for (int i = 0; i < kRing; ++i)
+      if (i < kSlots) ring[i] = frag(i);
+
+    float mx = 0.f, rs[2] = {0.f, 0.f}, p_even = 0.f;
+    bool move = false;
+    // Softmax work of slot m.  Every chunk hands its results to an empty asm statement, which keeps the
+    // optimiser from moving the arithmetic out of its slot (the results are only consumed a stage later).
+    auto softmax_chunk = [&](auto m_tag) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_tag)::value;
+      if constexpr (m < kMaxSlots) {
+        constexpr int per = 8 / kMaxSlots;  // pairs per slot
+        static_for<per>([&](auto i_tag) {
+          constexpr int v = 2 * (m * per + decltype(i_tag)::value);
+          if constexpr (v == 0) mx = max2_raw(st[kPar][0], st[kPar][1]);
+          else mx = max3_raw(mx, st[kPar][v], st[kPar][v + 1]);
+        });
+        asm volatile("" : "+v"(mx));
+      } else if constexpr (m == kMaxSlots) {
+        mx = max_with_partner_half_raw(mx);
+        move = (mx - m_ref) * scale_log2e > kLazyLog2;  // lazy reference point, as in the plain form
+        asm volatile("" : "+v"(mx));
+      } else if constexpr (m == kMaxSlots + 1) {
+        const float m_new = move ? mx : m_ref;
+        const float mc_new = m_new * scale_log2e;
+        alpha_pend = move ? __builtin_amdgcn_exp2f(mc_ref - mc_new) : 1.0f;  // exactly 1 for a row that stays
+        m_ref = m_new;
+        mc_ref = mc_new;
+        l_run *= alpha_pend;
+        asm volatile("" : "+v"(alpha_pend), "+v"(mc_ref), "+v"(l_run));
+        rescale_pend = __builtin_amdgcn_ballot_w64(move) != 0;
+      } else if constexpr (m < kFull) {
+        constexpr int c = m - kExpFirst;
+        static_for<16>([&](auto e_tag) {
+          constexpr int v = decltype(e_tag)::value;
+          if constexpr (v * kExpSlots / 16 == c) {
+            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kPar][v], scale_log2e, -mc_ref));
+            rs[v & 1] += pv;  // fp32 rowsum of the unrounded P~
+            asm volatile("" : "+v"(rs[v & 1]));
+            if constexpr ((v & 1) == 0) {
+              p_even = pv;
+            } else {
+              uint32_t packed = E::pack2(p_even, pv);
+              asm volatile("" : "+v"(packed));
+              pbuf[kPar][v / 8][(v % 8) / 2] = packed;
+            }
+          }
+        });
+      }
+    };
+
+    static_for<kSlots>([&](auto i_tag) {
+      constexpr int i = decltype(i_tag)::value;
+      constexpr bool second = (kG2 && kG1) ? (i & 1) == 0 : kG2;
+      constexpr int idx = (kG2 && kG1) ? i / 2 : i;
+      if constexpr (second) {
+        constexpr int t = idx / kDBlocks, db = idx % kDBlocks;
+        ot[db] = E::mfma(ring[i % kRing], pbuf[kPar ^ 1][t], ot[db]);
+      } else if constexpr (idx == 0) {
+        f32x16 zero;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+        st[kPar ^ 1] = E::mfma(ring[i % kRing], qf[idx], zero);
+      } else {
+        st[kPar ^ 1] = E::mfma(ring[i % kRing], qf[idx], st[kPar ^ 1]);
+      }
+      if constexpr (i + kRing < kSlots) ring[i % kRing] = frag(i + kRing);
+      if constexpr (kSm) softmax_chunk(i_tag);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if constexpr (kSm) {
+      // a stage without one of the products has fewer slots than chunks: the rest runs back to back
+      static_for<kFull - kSlots>([&](auto i_tag) {
+        softmax_chunk(std::integral_constant<int, decltype(i_tag)::value + kSlots>{});
+      });
+      l_run += rs[0] + rs[1];
+    }
+  };
+
   // LDS schedule.  K tile t lives in k_lds[t % kNBuf], V tile t in v_lds[t % kNBuf].  Iteration j reads
   // V tile j and K tile j+1 and ends with the one barrier per tile; after that barrier those two tiles are
   // dead and their buffers are refilled with K tile j+1+kNBuf and V tile j+kNBuf.  The loads needed by
@@ -471,11 +608,65 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
     __builtin_amdgcn_s_waitcnt(kWaitAll);
     __syncthreads();
-    gemm1(k_lds0);
-    __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
-    if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
-    if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
+    if constexpr (kPipe) {
+      stage_in(false_type{}, v_rsrc, 1, v_lds1);  // n_tiles >= 2; waited for by the first barrier of the pipeline
+    } else {
+      gemm1(k_lds0);
+      __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
+      if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
+      if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
+    }
 
+    if constexpr (kPipe) {
+      // Stage pipeline.  Stage (t, h) is the h-th half of K/V tile t.  Step t = the stages (t-1, 1) and (t, 0): it
+      // reads K tile t (for S of stages (t,0) and (t,1)) and V tile t-1 (for the P~ of stages (t-1,0), (t-1,1)),
+      // and ends with the one barrier per tile, after which both are dead and are refilled with K tile t+2 and
+      // V tile t+1.  What step t+1 reads was issued one barrier earlier, so each barrier waits for everything.
+      using par0 = std::integral_constant<int, 0>;
+      using par1 = std::integral_constant<int, 1>;
+      constexpr int kHalf = 32 * D;  // elements of half a tile
+      alpha_pend = 1.f;
+      rescale_pend = false;
+      // visible key count of a stage, relative to its first key, minus this lane's 4 hh; only meaningful for the
+      // last two tiles (the others are never masked)
+      auto visible_of = [&](int t, int h) __attribute__((always_inline)) -> int {
+        int visible = kCausal ? wave * 32 + r - 4 * hh - (t - (n_tiles - 2)) * kBc - 32 * h
+                              : Nk - 1 - t * kBc - 32 * h - 4 * hh;
+        if constexpr (kCausal || kRagged) asm volatile("" : "+v"(visible));
+        return visible;
+      };
+      auto step_end = [&](int t) __attribute__((always_inline)) {  // t: the K tile this step has read
+        __builtin_amdgcn_s_waitcnt(kWaitAll);
+        __syncthreads();
+        if (t + 2 < n_tiles) stage_in(true_type{}, k_rsrc, t + 2, k_buf[t & 1]);
+        if (t >= 1 && t + 1 < n_tiles) stage_in(false_type{}, v_rsrc, t + 1, v_buf[(t + 1) & 1]);
+      };
+      // prologue (K tile 0 has been consumed up to its first half by gemm1's replacement below)
+      // Step 0: S of stage (0,0) alone, then stage (0,0): softmax, S of stage (0,1); no GEMM-II yet.
+      stage(false_type{}, true_type{}, false_type{}, par1{}, false, 0, v_lds0, k_lds0);            // S_(0,0) -> st[0]
+      stage(false_type{}, true_type{}, true_type{}, par0{}, n_tiles == 2, visible_of(0, 0), v_lds0, k_lds0 + kHalf);
+      step_end(0);
+      int t = 1;
+      for (; t + 1 < n_tiles; t += 2) {
+        const bool m1 = t + 1 >= n_tiles - 1;  // tile t-1 >= n_tiles - 2
+        const bool m2 = t + 2 >= n_tiles - 1;
+        // step t (odd): K tile t in k_lds1, V tile t-1 in v_lds0
+        stage(true_type{}, true_type{}, true_type{}, par1{}, m1, visible_of(t - 1, 1), v_lds0, k_lds1);
+        stage(true_type{}, true_type{}, true_type{}, par0{}, m2 && t >= n_tiles - 2, visible_of(t, 0), v_lds0 + kHalf, k_lds1 + kHalf);
+        step_end(t);
+        // step t+1 (even): K tile t+1 in k_lds0, V tile t in v_lds1
+        stage(true_type{}, true_type{}, true_type{}, par1{}, t >= n_tiles - 2, visible_of(t, 1), v_lds1, k_lds0);
+        stage(true_type{}, true_type{}, true_type{}, par0{}, t + 1 >= n_tiles - 2, visible_of(t + 1, 0), v_lds1 + kHalf, k_lds0 + kHalf);
+        step_end(t + 1);
+      }
+      // last step t = n_tiles - 1 (odd): K tile n-1 in k_lds1, V tile n-2 in v_lds0
+      stage(true_type{}, true_type{}, true_type{}, par1{}, true, visible_of(t - 1, 1), v_lds0, k_lds1);
+      stage(true_type{}, true_type{}, true_type{}, par0{}, true, visible_of(t, 0), v_lds0 + kHalf, k_lds1 + kHalf);
+      step_end(t);
+      // stage (n-1, 1): softmax and O += P~_(n-1,0) V; then the draining product O += P~_(n-1,1) V
+      stage(true_type{}, false_type{}, true_type{}, par1{}, true, visible_of(t, 1), v_lds1, k_lds0);
+      stage(true_type{}, false_type{}, false_type{}, par0{}, false, 0, v_lds1 + kHalf, k_lds0);
+    } else {
     int j = 0;
     for (; j + kNBuf < n_tiles; j += kNBuf) {  // every barrier of these iterations issues its full set of loads
       static_for<kNBuf>([&](auto t) {
@@ -503,6 +694,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
         iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
       }
     });
+    }  // !kPipe
 
     // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
     const float l_tot = sum_with_partner_half(l_run);
@@ -879,10 +1071,10 @@ __global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_
 }
 
 // One instantiation of the 32-row kernel.
-template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
+template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged, bool kPipe = false>
 void launch_rows32(const void* Q, const void* K, const void* V, void* O, float* LSE, int H, int Nq, int Nk,
                    float scale_log2e, int n_qtiles, int total, hipStream_t stream) {
-  hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged>), dim3((unsigned)total), dim3(kWv * 64), 0,
+  hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged, kPipe>), dim3((unsigned)total), dim3(kWv * 64), 0,
                      stream, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                      static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles,
                      total);
@@ -914,6 +1106,12 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
     } else {
       return FA2_ERR_UNSUPPORTED;
     }
+  } else if (variant == FA2_VARIANT_PIPE) {  // whole tiles, no mask, d <= 128 (checked by the caller)
+    if constexpr (D <= 128) {
+      launch_rows32<DT, D, 4, 2, false, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+    } else {
+      return FA2_ERR_UNSUPPORTED;
+    }
   } else if (causal) {
     if (ragged) launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
     else launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
@@ -935,7 +1133,7 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(LSE, 4))
     return FA2_ERR_INVALID_ARG;
   if (variant != FA2_VARIANT_AUTO && variant != FA2_VARIANT_NARROW && variant != FA2_VARIANT_WIDE &&
-      variant != FA2_VARIANT_NARROW8)
+      variant != FA2_VARIANT_NARROW8 && variant != FA2_VARIANT_PIPE)
     return FA2_ERR_INVALID_ARG;
   if (mask != FA2_MASK_NONE && mask != FA2_MASK_CAUSAL) return FA2_ERR_INVALID_ARG;
   if (dtype != FA2_FP16 && dtype != FA2_BF16) return FA2_ERR_UNSUPPORTED;
@@ -948,13 +1146,15 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if ((unsigned long long)n_max * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32))
     return FA2_ERR_UNSUPPORTED;
   if (variant == FA2_VARIANT_AUTO) {
-    // Measured on MI355X with N(0,1) inputs, the 4-wavefront, 128-row shape is the fastest of the three on
-    // every workload shape tried (N = 512 .. 16384, d = 64 and 128); the others stay selectable for sweeps.
+    // Measured on MI355X with N(0,1) inputs, the 4-wavefront, 128-row shape with block-wise softmax is the
+    // fastest on every workload shape tried (N = 512 .. 16384, d = 64 and 128); the others stay selectable
+    // for sweeps.
     variant = FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {
-    // the 256-row shapes exist for tile-shape sweeps: whole tiles, square, unmasked, d <= 128
-    if (Nq != Nk || Nq % kWideBr != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
+    // the other shapes and schedules exist for sweeps: whole tiles, square, unmasked, d <= 128
+    const int rows = variant == FA2_VARIANT_PIPE ? kBr : kWideBr;
+    if (Nq != Nk || Nq % rows != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {

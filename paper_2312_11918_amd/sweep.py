@@ -3,7 +3,7 @@ on a list of attention shapes and prints a table of forward TFLOP/s (4*B*H*N^2*d
 
 Usage:  python -m paper_2312_11918_amd.sweep [--paper] [--workloads] [--iters K]
 
-  --paper      the paper's benchmark shapes: batch 4, N = 4096, (heads, head dim) = (32, 64), (16, 128), fp16
+  --paper      the paper's benchmark shapes: batch 4, N = 4096, (heads, head dim) = (32, 64), (16, 128), (8, 256), fp16
   --workloads  the five synthetic workloads of this repository (the default if nothing is selected)
 
 Inputs are i.i.d. N(0,1), seeded; every variant's output is checked to be finite.
@@ -15,7 +15,7 @@ import sys
 
 import numpy as np
 
-VARIANTS = [("narrow 4x32", 1), ("narrow8 8x32", 3), ("wide 4x64", 2)]
+VARIANTS = [("narrow 4x32", 1), ("narrow8 8x32", 3), ("wide 4x64", 2), ("narrow 4x32, staged softmax", 4)]
 PEAK = 2516.6
 
 
@@ -58,7 +58,8 @@ def main(argv=None):
     shapes = []
     if args.paper:
         shapes += [("paper B4 H32 N4096 d64 fp16", 4, 32, 4096, 64, "fp16", 0.0, 1.0, 4096 + 64),
-                   ("paper B4 H16 N4096 d128 fp16", 4, 16, 4096, 128, "fp16", 0.0, 1.0, 4096 + 128)]
+                   ("paper B4 H16 N4096 d128 fp16", 4, 16, 4096, 128, "fp16", 0.0, 1.0, 4096 + 128),
+                   ("paper B4 H8 N4096 d256 fp16", 4, 8, 4096, 256, "fp16", 0.0, 1.0, 4096 + 256)]
     if args.workloads or not shapes:
         for i in sorted(workloads.CONFIGS):
             w = workloads.CONFIGS[i]
@@ -74,7 +75,8 @@ def main(argv=None):
         iters = args.iters or int(min(max(50e-3 / (flops / 0.8e15), 5), 500))
         cells = []
         for _, variant in VARIANTS:
-            if variant != 1 and N % 256 != 0:
+            # only the default shape runs d = 256; the 256-row shapes need whole 256-row tiles
+            if variant != 1 and (d > 128 or (variant in (2, 3) and N % 256 != 0)):
                 cells.append(None)
                 continue
             ms = _time(q, k, v, scale, variant, iters)
