@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0
 HEADLINE = 3
 
 # HBM bytes per launch measured with rocprofv3 --pmc (profiles/fa2_fwd_fp16_d128_B8_H16_N2048.txt):
-# FETCH_SIZE 98402.31 KiB x 2.0 (a plain 64 MiB copy reads 65536 KiB and the counter shows 32787) plus
+# FETCH_SIZE 98401.30 KiB x 2.0 (a plain 64 MiB copy reads 65536 KiB and the counter shows 32787) plus
 # WRITE_SIZE 66560.00 KiB x 1.0.  Equal to the algorithmic bytes: Q, K, V read once, O and LSE written once.
-MEASURED_TRAFFIC_BYTES = {"B8_H16_N2048_d128_fp16": int((98402.31 * 2.0 + 66560.00) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"B8_H16_N2048_d128_fp16": int((98401.30 * 2.0 + 66560.00) * 1024)}
 
 
 _CUSTOM = {}
