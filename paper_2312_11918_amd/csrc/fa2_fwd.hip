@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
 #include <type_traits>
 #include <utility>
 
@@ -1070,14 +1071,24 @@ __global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_
   }
 }
 
+// Enqueues `kernel` and reports this launch's own status (not whatever error an earlier, unrelated HIP call left).
+template <class... Params, class... Args>
+int enqueue(void (*kernel)(Params...), int grid, int block, hipStream_t stream, Args... args) {
+  std::tuple<Params...> values{static_cast<Params>(args)...};
+  void* ptrs[sizeof...(Params)];
+  std::apply([&](auto&... v) { int i = 0; ((ptrs[i++] = &v), ...); }, values);
+  const hipError_t err = hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3((unsigned)grid), dim3((unsigned)block),
+                                         ptrs, 0, stream);
+  return err == hipSuccess ? FA2_OK : FA2_ERR_LAUNCH;
+}
+
 // One instantiation of the 32-row kernel.
 template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged, bool kPipe = false>
-void launch_rows32(const void* Q, const void* K, const void* V, void* O, float* LSE, int H, int Nq, int Nk,
-                   float scale_log2e, int n_qtiles, int total, hipStream_t stream) {
-  hipLaunchKernelGGL((fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged, kPipe>), dim3((unsigned)total), dim3(kWv * 64), 0,
-                     stream, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                     static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles,
-                     total);
+int launch_rows32(const void* Q, const void* K, const void* V, void* O, float* LSE, int H, int Nq, int Nk,
+                  float scale_log2e, int n_qtiles, int total, hipStream_t stream) {
+  return enqueue(fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged, kPipe>, total, kWv * 64, stream,
+                 static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V),
+                 static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles, total);
 }
 
 template <int DT, int D>
@@ -1096,30 +1107,26 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   if (rows256) {  // exact tiles, no mask, d <= 128 (checked by the caller)
     if constexpr (D <= 128) {
       if (variant == FA2_VARIANT_WIDE) {
-        hipLaunchKernelGGL((fa2_fwd_wide_kernel<DT, D>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                           static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                           static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE, H, Nq, scale_log2e,
-                           n_qtiles, total);
-      } else {
-        launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+        return enqueue(fa2_fwd_wide_kernel<DT, D>, total, kThreads, stream, static_cast<const uint16_t*>(Q),
+                       static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE,
+                       H, Nq, scale_log2e, n_qtiles, total);
       }
+      return launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
     } else {
       return FA2_ERR_UNSUPPORTED;
     }
   } else if (variant == FA2_VARIANT_PIPE) {  // whole tiles, no mask, d <= 128 (checked by the caller)
     if constexpr (D <= 128) {
-      launch_rows32<DT, D, 4, 2, false, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+      return launch_rows32<DT, D, 4, 2, false, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
     } else {
       return FA2_ERR_UNSUPPORTED;
     }
   } else if (causal) {
-    if (ragged) launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
-    else launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
-  } else {
-    if (ragged) launch_rows32<DT, D, 4, 2, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
-    else launch_rows32<DT, D, 4, 2, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+    return ragged ? launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
+                  : launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
   }
-  return hipGetLastError() == hipSuccess ? FA2_OK : FA2_ERR_LAUNCH;
+  return ragged ? launch_rows32<DT, D, 4, 2, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
+                : launch_rows32<DT, D, 4, 2, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
 }
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
