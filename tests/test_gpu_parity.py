@@ -239,3 +239,36 @@ def test_runs_on_a_side_stream_and_is_deterministic():
     s.synchronize()
     torch.cuda.synchronize()
     assert torch.equal(o0, o1) and torch.equal(l0, l1)
+
+
+def test_launch_can_be_captured_in_a_hip_graph_and_replayed():
+    # fa2_fwd only enqueues a kernel, so a stream capture records it; every replay must equal an eager launch on
+    # the inputs that are in the buffers at that time.  (Nothing but the kernel is captured: no memset, no copy.)
+    torch = _torch()
+    B, H, N, d = 2, 3, 384, 128
+    print("graph capture and replay", flush=True)
+    q, k, v = (torch.empty((B, N, H, d), dtype=torch.float16, device="cuda") for _ in range(3))
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+
+    def fill(seed):
+        qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", seed)
+        for t, x in ((q, qb), (k, kb), (v, vb)):
+            t.copy_(_to_device(x, "fp16"))
+        return qb, kb, vb
+
+    fill(50)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fa2.fa2_fwd(q, k, v, 0.1, out=o, lse=lse, causal=True)
+    for seed in (51, 52, 53):
+        qb, kb, vb = fill(seed)
+        o.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        o_eager, lse_eager = fa2.fa2_fwd(q, k, v, 0.1, causal=True)
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_eager) and torch.equal(lse, lse_eager), f"replay with seed {seed} differs from eager"
+        o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), 0.1, causal=True)
+        _check(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, f"graph replay seed {seed}")
