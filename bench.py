@@ -66,14 +66,22 @@ def _device_tensors(index):
     return w, q, k, v
 
 
-def _time_workload(index, steps, warmup, causal=False):
-    """Times `steps` back-to-back launches with HIP events on the launch stream; returns ms per step."""
+def _prepare(index):
+    """Device tensors of a workload plus its output buffers."""
     import torch
-    import paper_2312_11918_amd as fa2
 
     w, q, k, v = _device_tensors(index)
     o = torch.empty_like(q)
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    return w, q, k, v, o, lse
+
+
+def _time_prepared(prep, steps, warmup, causal=False):
+    """Times `steps` back-to-back launches with HIP events on the launch stream; returns (ms per step, wall ms)."""
+    import torch
+    import paper_2312_11918_amd as fa2
+
+    w, q, k, v, o, lse = prep
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream, causal=causal)
@@ -88,9 +96,59 @@ def _time_workload(index, steps, warmup, causal=False):
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
     assert bool(torch.isfinite(o).all()), "non-finite output"
-    del q, k, v, o, lse
+    return ev_ms / steps, wall_ms / steps
+
+
+def _time_workload(index, steps, warmup, causal=False):
+    """Prepares the workload, times it, frees it; returns (workload, ms per step, wall ms per step)."""
+    import torch
+
+    prep = _prepare(index)
+    ms, wall_ms = _time_prepared(prep, steps, warmup, causal)
+    w = prep[0]
+    del prep
     torch.cuda.empty_cache()
-    return w, ev_ms / steps, wall_ms / steps
+    return w, ms, wall_ms
+
+
+def _mfma_roof(kind, dtype, seed=7):
+    """MFMA-only throughput on this box with `kind` operands ("normal": N(0,1) values as in the workloads,
+    "constant": all ones), and the engine clock during that run.  Uses libfa2_probe (include/fa2_probe.h)."""
+    import torch
+    import paper_2312_11918_amd as fa2
+    from paper_2312_11918_amd import workloads
+
+    n16 = fa2.FA2_PROBE_OPERAND_BYTES // 2
+    if kind == "normal":
+        vals = np.random.Generator(np.random.PCG64(seed)).standard_normal(n16, dtype=np.float32)
+    else:
+        vals = np.ones(n16, dtype=np.float32)
+    ops = torch.from_numpy(workloads.round_to_bits(vals, dtype).view(np.int16)).cuda()
+    ticks = torch.zeros(4, dtype=torch.int64, device="cuda")
+    sink = torch.empty(fa2.FA2_PROBE_WORKGROUPS * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    dt = fa2.FA2_FP16 if dtype == "fp16" else fa2.FA2_BF16
+    iters = 20000  # 3.4e12 FLOP per launch, about 2 ms
+
+    def launch():
+        rc = fa2.fa2_probe_mfma_raw(ops.data_ptr(), ticks.data_ptr(), sink.data_ptr(), dt, iters, stream.cuda_stream)
+        assert rc == 0, f"fa2_probe_mfma returned {rc}"
+
+    for _ in range(3):
+        launch()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record(stream)
+    for _ in range(reps):
+        launch()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops = fa2.FA2_PROBE_WORKGROUPS * 4 * iters * fa2.FA2_PROBE_MFMA_PER_ITER * 32768.0
+    t = ticks.cpu().numpy()
+    mhz = 100.0 * float(t[1] - t[0]) / max(float(t[3] - t[2]), 1.0)
+    return {"tflops": round(flops / (ms * 1e-3) / 1e12, 1), "clock_mhz": round(mhz)}
 
 
 def _cpu_baseline(index, target_seconds=15.0):
@@ -127,7 +185,9 @@ def main():
     ap.add_argument("--causal", action="store_true",
                     help="time fa2_fwd_masked with the causal mask; FLOPs are then counted as 2*B*H*N^2*d")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
-    ap.add_argument("--only-headline", action="store_true", help="do not time the other workloads")
+    ap.add_argument("--no-mfma-roof", action="store_true", help="skip the MFMA-only roof measurement")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="time the headline launch only: no other workloads, no causal run, no MFMA roof, no extra regions")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="K",
                     help="first run K plain device copies of the headline Q tensor (a kernel of known HBM "
                          "traffic, for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
@@ -159,7 +219,9 @@ def main():
               f"(reads {qc.numel() * 2} B, writes {qc.numel() * 2} B each)", file=sys.stderr)
         del qc, dst
 
-    w, ms, wall_ms = _time_workload(args.workload, args.steps, args.warmup, causal=args.causal)
+    prep = _prepare(args.workload)
+    w = prep[0]
+    ms, wall_ms = _time_prepared(prep, args.steps, args.warmup, causal=args.causal)
     flops = w.flops * (0.5 if args.causal else 1.0)
     tflops = flops / (ms * 1e-3) / 1e12
     alg_bytes = 4 * w.B * w.H * w.N * w.d * 2 + 4 * w.B * w.H * w.N
@@ -183,10 +245,22 @@ def main():
     # the same shape under the causal mask (fa2_fwd_masked); FLOPs counted as half of the unmasked product
     causal = None
     if not args.only_headline:
-        _, cms, _ = _time_workload(args.workload, args.steps, args.warmup, causal=True)
+        cms, _ = _time_prepared(prep, args.steps, args.warmup, causal=True)
         ctf = 0.5 * w.flops / (cms * 1e-3) / 1e12
         causal = {"ms": round(cms, 5), "tflops": round(ctf, 2), "frac_mfma_peak": round(ctf / MFMA_PEAK_TFLOPS, 4),
                   "flops_counted": "2*B*H*N^2*d"}
+
+    # the matrix-core roof of this box as measured now, on the workload's kind of operands and on constants
+    roof = None
+    if not (args.no_mfma_roof or args.only_headline):
+        roof = {"normal_operands": _mfma_roof("normal", w.dtype), "constant_operands": _mfma_roof("constant", w.dtype)}
+
+    # a few more timed regions of the same launch: spread of the measurement (not used for `value`)
+    regions = None
+    if not args.only_headline:
+        regions = sorted(_time_prepared(prep, args.steps, 0, causal=args.causal)[0] for _ in range(5))
+    del prep
+    torch.cuda.empty_cache()
 
     out = {
         "metric": "attention fwd TFLOP/s (2*B*H*N^2*d, causal)" if args.causal else "attention fwd TFLOP/s (4*B*H*N^2*d)",
@@ -208,7 +282,12 @@ def main():
                      "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
                      "traffic": None if args.causal else MEASURED_TRAFFIC_BYTES.get(w.name),
                      "algorithmic_flops_per_launch": flops, "algorithmic_hbm_bytes_per_launch": alg_bytes,
-                     "kernel": "fa2_fwd_kernel", "kernel_ms": round(ms, 5)},
+                     "kernel": "fa2_fwd_kernel", "kernel_ms": round(ms, 5),
+                     "mfma_roof_measured": roof,
+                     "frac_of_measured_roof": None if roof is None else round(tflops / roof["normal_operands"]["tflops"], 4)},
+        "timing_regions": None if regions is None else {
+            "n": 5, "steps_each": args.steps, "best_ms": round(regions[0], 5), "median_ms": round(regions[2], 5),
+            "worst_ms": round(regions[4], 5)},
         "workloads": per_workload,
         "causal_same_shape": causal,
         "paper_context": "H100 PCIe, fp16: 295.7 TFLOP/s best at d=128 (Table 1), 39% of its 756 TFLOP/s peak; not a target",

@@ -24,7 +24,9 @@ FA2_MASK_CAUSAL = 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libfa2.so")
+_PROBE_PATH = os.path.join(_PKG, "libfa2_probe.so")
 _lib = None
+_probe = None
 
 
 class Fa2Error(RuntimeError):
@@ -61,6 +63,34 @@ def load_library():
         lib.fa2_version.restype = ci
         _lib = lib
     return _lib
+
+
+def probe_library_path() -> str:
+    return _PROBE_PATH
+
+
+def load_probe_library():
+    """Load libfa2_probe.so (the MFMA roof probe, see include/fa2_probe.h).  A missing library is an error."""
+    global _probe
+    if _probe is None:
+        if not os.path.exists(_PROBE_PATH):
+            raise FileNotFoundError(f"{_PROBE_PATH} is not built; run `python -m paper_2312_11918_amd.build`")
+        lib = ctypes.CDLL(_PROBE_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.fa2_probe_mfma.argtypes = [vp, vp, vp, ci, ci, vp]
+        lib.fa2_probe_mfma.restype = ci
+        _probe = lib
+    return _probe
+
+
+FA2_PROBE_WORKGROUPS = 512
+FA2_PROBE_MFMA_PER_ITER = 16
+FA2_PROBE_OPERAND_BYTES = 256 * 4 * 2 * 16
+
+
+def fa2_probe_mfma_raw(operands_ptr, ticks_ptr, sink_ptr, dtype, iters, stream=None) -> int:
+    """Call ``fa2_probe_mfma`` with raw device addresses; returns the C return code."""
+    return int(load_probe_library().fa2_probe_mfma(operands_ptr, ticks_ptr, sink_ptr, int(dtype), int(iters), stream))
 
 
 def fa2_strerror(code: int) -> str:

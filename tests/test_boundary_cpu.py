@@ -27,6 +27,21 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), f"{name} is declared in include/fa2.h but not exported"
 
 
+def test_probe_library_exports_what_its_header_declares():
+    text = open(os.path.join(ROOT, "include", "fa2_probe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(fa2_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["fa2_probe_mfma"]
+    lib = ctypes.CDLL(fa2.probe_library_path())
+    for name in names:
+        assert hasattr(lib, name)
+    # bad arguments are refused before any HIP call
+    assert fa2.fa2_probe_mfma_raw(None, 0x1000, 0x1000, 0, 10) == -1
+    assert fa2.fa2_probe_mfma_raw(0x1000, 0x1000, 0x1000, 0, 0) == -1
+    assert fa2.fa2_probe_mfma_raw(0x1008, 0x1000, 0x1000, 0, 10) == -1
+    assert fa2.fa2_probe_mfma_raw(0x1000, 0x1000, 0x1000, 5, 10) == -1
+
+
 def test_version_and_strerror():
     assert fa2.fa2_version() >= 100
     for code in (fa2.FA2_OK, fa2.FA2_ERR_INVALID_ARG, fa2.FA2_ERR_UNSUPPORTED, fa2.FA2_ERR_LAUNCH, 12345):

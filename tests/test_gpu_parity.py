@@ -291,3 +291,30 @@ def test_parity_over_softmax_scales(scale, dtype):
         assert np.max(np.abs(lse - lse_ref)) <= TOL_LSE_MAX
     else:
         _check(o, lse, o_ref, lse_ref, f"scale {scale} {dtype}")
+
+
+def test_mfma_roof_probe_reports_a_plausible_clock_and_rate():
+    # the measurement aid of bench.py: MFMA-only launch on supplied operands, engine clock from two counters
+    torch = _torch()
+    print("mfma roof probe", flush=True)
+    n16 = fa2.FA2_PROBE_OPERAND_BYTES // 2
+    vals = np.random.Generator(np.random.PCG64(3)).standard_normal(n16, dtype=np.float32)
+    ops = torch.from_numpy(workloads.round_to_bits(vals, "fp16").view(np.int16)).cuda()
+    ticks = torch.zeros(4, dtype=torch.int64, device="cuda")
+    sink = torch.full((fa2.FA2_PROBE_WORKGROUPS * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    iters = 4000
+    assert fa2.fa2_probe_mfma_raw(ops.data_ptr(), ticks.data_ptr(), sink.data_ptr(), fa2.FA2_FP16, iters, s) == 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    assert fa2.fa2_probe_mfma_raw(ops.data_ptr(), ticks.data_ptr(), sink.data_ptr(), fa2.FA2_FP16, iters, s) == 0
+    e1.record()
+    torch.cuda.synchronize()
+    t = ticks.cpu().numpy()
+    mhz = 100.0 * float(t[1] - t[0]) / float(t[3] - t[2])
+    tflops = fa2.FA2_PROBE_WORKGROUPS * 4 * iters * fa2.FA2_PROBE_MFMA_PER_ITER * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    print(f"probe: {tflops:.0f} TFLOP/s at {mhz:.0f} MHz", flush=True)
+    assert 500.0 <= mhz <= 2600.0
+    assert 800.0 <= tflops <= 2600.0
+    assert bool(torch.isfinite(sink).all())
