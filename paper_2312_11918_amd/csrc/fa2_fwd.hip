@@ -145,7 +145,8 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 // kCausal applies the optional mask of S (Section 2 of the paper: entries of S may be set to -inf before the
 // softmax; here those with key index > query index).  A Q tile then stops at its diagonal: it visits
 // (qt+1)*kNBuf K/V tiles instead of N/kBc, only the last kNBuf of them straddle the diagonal and need the
-// element-wise mask, and Q tiles are dealt heaviest first.
+// element-wise mask, and a workgroup takes two Q tiles of one head, the p-th from the end and the p-th from the
+// start, whose tile counts add up to the same number for every p.
 //
 // kRagged lifts the restriction to whole tiles: Nq query rows and Nk keys of any size >= 1.  Query rows past
 // Nq-1 are computed from a copy of the last row and not stored; K/V rows past Nk-1 are staged as copies of
