@@ -318,3 +318,44 @@ def test_mfma_roof_probe_reports_a_plausible_clock_and_rate():
     assert 500.0 <= mhz <= 2600.0
     assert 800.0 <= tflops <= 2600.0
     assert bool(torch.isfinite(sink).all())
+
+
+def test_concurrent_launches_from_threads_on_their_own_streams():
+    # the library keeps no state: launches from several host threads, each on a stream of its own, must give the
+    # bits of the same launches made one after the other
+    import threading
+    torch = _torch()
+    print("concurrent launches", flush=True)
+    shapes = [(2, 3, 512, 128, "fp16", False), (1, 4, 1000, 64, "bf16", False), (2, 2, 640, 128, "fp16", True),
+              (1, 2, 768, 256, "fp16", False)]
+    jobs = []
+    for i, (B, H, N, d, dtype, causal) in enumerate(shapes):
+        qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, 700 + i)
+        q, k, v = (_to_device(x, dtype) for x in (qb, kb, vb))
+        o_seq, lse_seq = fa2.fa2_fwd(q, k, v, 0.1, causal=causal)
+        jobs.append((q, k, v, causal, o_seq, lse_seq))
+    torch.cuda.synchronize()
+    results = [None] * len(jobs)
+    errors = []
+
+    def work(i):
+        try:
+            q, k, v, causal, _, _ = jobs[i]
+            s = torch.cuda.Stream()
+            outs = []
+            for _ in range(20):
+                outs.append(fa2.fa2_fwd(q, k, v, 0.1, causal=causal, stream=s))
+            s.synchronize()
+            results[i] = outs
+        except Exception as e:  # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i, (_, _, _, _, o_seq, lse_seq) in enumerate(jobs):
+        for o, lse in results[i]:
+            assert torch.equal(o, o_seq) and torch.equal(lse, lse_seq), f"job {i} differs under concurrency"
