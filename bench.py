@@ -28,10 +28,19 @@ MFMA_PEAK_TFLOPS = 2516.6      # MI355X dense fp16 = bf16 matrix peak (256 CU x 
 HBM_PEAK_GBS = 8000.0
 HEADLINE = 3
 
-# HBM bytes per launch measured with rocprofv3 --pmc (profiles/fa2_fwd_fp16_d128_B8_H16_N2048.txt):
-# FETCH_SIZE 98401.30 KiB x 2.0 (a plain 64 MiB copy reads 65536 KiB and the counter shows 32787) plus
-# WRITE_SIZE 66560.00 KiB x 1.0.  Equal to the algorithmic bytes: Q, K, V read once, O and LSE written once.
-MEASURED_TRAFFIC_BYTES = {"B8_H16_N2048_d128_fp16": int((98401.30 * 2.0 + 66560.00) * 1024)}
+VALU_LANES_PER_CLK_CU = 64.0   # plain (unpacked) fp32 vector rate: 4 SIMDs x 16 lanes per clock
+ENGINE_CLOCK_HZ = 2.4e9
+N_CUS = 256
+# Vector-pipe issue slots per element of S in the softmax of the kernel as built: fma (1) + exp2 (2: the
+# exponential is a half-rate instruction) + rowsum add (1) + half a 16-bit pack (0.5) + half a 3-input max (0.5).
+SOFTMAX_VALU_SLOTS_PER_ELEMENT = 5.0
+
+# HBM bytes per launch as profiled with rocprofv3 --pmc (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0, factors from a
+# plain 64 MiB device copy in the same runs); not measured by this script.  Each entry names the summary it is from.
+PROFILED_TRAFFIC = {
+    "B8_H16_N2048_d128_fp16": {"bytes": int((98401.30 * 2.0 + 66560.00) * 1024),
+                               "profile": "profiles/fa2_fwd_fp16_d128_B8_H16_N2048.txt"},
+}
 
 
 _CUSTOM = {}
@@ -76,39 +85,89 @@ def _prepare(index):
     return w, q, k, v, o, lse
 
 
-def _time_prepared(prep, steps, warmup, causal=False):
-    """Times `steps` back-to-back launches with HIP events on the launch stream; returns (ms per step, wall ms)."""
+def _launcher(prep, causal):
     import torch
     import paper_2312_11918_amd as fa2
 
     w, q, k, v, o, lse = prep
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream, causal=causal)
+
+    def run(n):
+        """n back-to-back launches between two HIP events recorded on the launch stream; returns ms per launch."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream, causal=causal)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    return run
+
+
+def _time_prepared(prep, steps, warmup, causal=False, n_regions=5, min_region_ms=50.0, settle_ms=100.0):
+    """Times one workload.  Returns a dict:
+      first_region_ms   ms per launch of the FIRST timed region: exactly `steps` launches right after `warmup`
+                        untimed ones (the clock and power state of the chip are still settling then);
+      regions_ms        ms per launch of `n_regions` further regions, each of max(steps, enough launches for
+                        `min_region_ms`), taken after at least `settle_ms` of launches and once two consecutive
+                        regions agree within 2 % (at most 20 tries);
+      ms                their median -- the figure reported as ms_per_step;
+      wall_ms           host wall clock per launch over the first region (launch overhead included).
+    """
+    import torch
+
+    run = _launcher(prep, causal)
+    for _ in range(max(warmup, 0)):
+        run(1)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
-        fa2.fa2_fwd(q, k, v, w.scale, out=o, lse=lse, stream=stream, causal=causal)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ev_ms = e0.elapsed_time(e1)
-    assert bool(torch.isfinite(o).all()), "non-finite output"
-    return ev_ms / steps, wall_ms / steps
+    first = run(steps)
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    n = max(steps, int(min_region_ms / max(first, 1e-4)) + 1)
+    spent, prev = first * steps, None
+    for _ in range(20 if n_regions > 0 else 0):
+        cur = run(n)
+        spent += cur * n
+        if spent >= settle_ms and prev is not None and abs(cur - prev) <= 0.02 * prev:
+            break
+        prev = cur
+    regions = [run(n) for _ in range(n_regions)]
+    assert bool(torch.isfinite(prep[4]).all()), "non-finite output"
+    return {"ms": float(np.median(regions)) if regions else first, "first_region_ms": first, "regions_ms": sorted(regions),
+            "launches_per_region": n, "wall_ms": wall_ms}
 
 
 def _time_workload(index, steps, warmup, causal=False):
-    """Prepares the workload, times it, frees it; returns (workload, ms per step, wall ms per step)."""
+    """Prepares the workload, times it, frees it; returns (workload, timing dict)."""
     import torch
 
     prep = _prepare(index)
-    ms, wall_ms = _time_prepared(prep, steps, warmup, causal)
+    t = _time_prepared(prep, steps, warmup, causal)
     w = prep[0]
     del prep
     torch.cuda.empty_cache()
-    return w, ms, wall_ms
+    return w, t
+
+
+def _roofs(w, ms, causal=False):
+    """The workload's throughput against the roofs that can bound it: the matrix cores (published dense peak), the
+    vector pipe (the softmax's issue slots; binds before the matrix cores when 4 d FLOPs per element of S take less
+    matrix time than the softmax takes vector time, i.e. for small d) and HBM (the algorithmic bytes at 8 TB/s)."""
+    flops = w.flops * (0.5 if causal else 1.0)
+    tf = flops / (ms * 1e-3) / 1e12
+    elements = w.B * w.H * float(w.N) ** 2 * (0.5 if causal else 1.0)
+    alu_elems_per_s = N_CUS * ENGINE_CLOCK_HZ * VALU_LANES_PER_CLK_CU / SOFTMAX_VALU_SLOTS_PER_ELEMENT
+    alu_roof_tf = alu_elems_per_s * 4.0 * w.d / 1e12      # the same FLOP count, at the rate the softmax allows
+    alg_bytes = 4 * w.B * w.H * w.N * w.d * 2 + 4 * w.B * w.H * w.N
+    hbm_ms = alg_bytes / (HBM_PEAK_GBS * 1e9) * 1e3
+    return {"tflops": round(tf, 2), "frac_mfma_peak": round(tf / MFMA_PEAK_TFLOPS, 4),
+            "alu_roof_tflops": round(alu_roof_tf, 1), "frac_alu_roof": round(tf / alu_roof_tf, 4),
+            "softmax_elements_per_s": round(elements / (ms * 1e-3), 0),
+            "hbm_gbs_algorithmic": round(alg_bytes / (ms * 1e-3) / 1e9, 1), "hbm_floor_ms": round(hbm_ms, 5),
+            "frac_hbm_roof": round(hbm_ms / ms, 4),
+            "binding_roof": min((("mfma", MFMA_PEAK_TFLOPS), ("alu", alu_roof_tf),
+                                 ("hbm", flops / (hbm_ms * 1e-3) / 1e12)), key=lambda r: r[1])[0]}
 
 
 def _mfma_roof(kind, dtype, seed=7):
@@ -187,7 +246,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-mfma-roof", action="store_true", help="skip the MFMA-only roof measurement")
     ap.add_argument("--only-headline", action="store_true",
-                    help="time the headline launch only: no other workloads, no causal run, no MFMA roof, no extra regions")
+                    help="time the headline launch only: no other workloads, no causal run, no MFMA roof")
+    ap.add_argument("--regions", type=int, default=5,
+                    help="timed regions after the first one; the reported value is their median (0: report the "
+                         "first region, for short profiler runs)")
+    ap.add_argument("--min-region-ms", type=float, default=50.0, help="minimum length of each of those regions")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="K",
                     help="first run K plain device copies of the headline Q tensor (a kernel of known HBM "
                          "traffic, for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
@@ -221,47 +284,47 @@ def main():
 
     prep = _prepare(args.workload)
     w = prep[0]
-    ms, wall_ms = _time_prepared(prep, args.steps, args.warmup, causal=args.causal)
+    t = _time_prepared(prep, args.steps, args.warmup, causal=args.causal, n_regions=args.regions,
+                       min_region_ms=args.min_region_ms)
+    ms = t["ms"]
     flops = w.flops * (0.5 if args.causal else 1.0)
     tflops = flops / (ms * 1e-3) / 1e12
     alg_bytes = 4 * w.B * w.H * w.N * w.d * 2 + 4 * w.B * w.H * w.N
+    roofs = _roofs(w, ms, args.causal)
 
     per_workload = {}
     if not args.only_headline:
         for idx in sorted(workloads.CONFIGS):
             if idx == args.workload:
-                wi, msi = w, ms
+                wi, ti = w, t
             else:
                 wi0 = workloads.CONFIGS[idx]
-                # about 50 ms of timed launches each
-                est = max(wi0.flops / 0.4e15, 20e-6)
-                si = int(min(max(50e-3 / est, 5), 1000))
-                wi, msi, _ = _time_workload(idx, si, max(3, si // 10))
-            tf = wi.flops / (msi * 1e-3) / 1e12
-            per_workload[wi.name] = {"ms": round(msi, 5), "tflops": round(tf, 2),
-                                     "frac_mfma_peak": round(tf / MFMA_PEAK_TFLOPS, 4),
-                                     "hbm_gbs_algorithmic": round((4 * wi.B * wi.H * wi.N * wi.d * 2 + 4 * wi.B * wi.H * wi.N) / (msi * 1e-3) / 1e9, 1)}
+                si = int(min(max(10e-3 / max(wi0.flops / 0.4e15, 20e-6), 5), 400))
+                wi, ti = _time_workload(idx, si, max(3, si // 10))
+            entry = {"ms": round(ti["ms"], 5), "first_region_ms": round(ti["first_region_ms"], 5),
+                     "launches_per_region": ti["launches_per_region"]}
+            entry.update(_roofs(wi, ti["ms"]))
+            prof = PROFILED_TRAFFIC.get(wi.name)
+            entry["traffic_profiled"] = None if prof is None else prof
+            per_workload[wi.name] = entry
 
     # the same shape under the causal mask (fa2_fwd_masked); FLOPs counted as half of the unmasked product
     causal = None
     if not args.only_headline:
-        cms, _ = _time_prepared(prep, args.steps, args.warmup, causal=True)
-        ctf = 0.5 * w.flops / (cms * 1e-3) / 1e12
-        causal = {"ms": round(cms, 5), "tflops": round(ctf, 2), "frac_mfma_peak": round(ctf / MFMA_PEAK_TFLOPS, 4),
+        ct = _time_prepared(prep, args.steps, args.warmup, causal=True, n_regions=args.regions,
+                            min_region_ms=args.min_region_ms)
+        causal = {"ms": round(ct["ms"], 5), "first_region_ms": round(ct["first_region_ms"], 5),
                   "flops_counted": "2*B*H*N^2*d"}
+        causal.update(_roofs(w, ct["ms"], causal=True))
 
     # the matrix-core roof of this box as measured now, on the workload's kind of operands and on constants
     roof = None
     if not (args.no_mfma_roof or args.only_headline):
         roof = {"normal_operands": _mfma_roof("normal", w.dtype), "constant_operands": _mfma_roof("constant", w.dtype)}
-
-    # a few more timed regions of the same launch: spread of the measurement (not used for `value`)
-    regions = None
-    if not args.only_headline:
-        regions = sorted(_time_prepared(prep, args.steps, 0, causal=args.causal)[0] for _ in range(5))
     del prep
     torch.cuda.empty_cache()
 
+    prof = None if args.causal else PROFILED_TRAFFIC.get(w.name)
     out = {
         "metric": "attention fwd TFLOP/s (2*B*H*N^2*d, causal)" if args.causal else "attention fwd TFLOP/s (4*B*H*N^2*d)",
         "value": round(tflops, 2),
@@ -270,7 +333,13 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms, 5),
-        "wall_ms_per_step": round(wall_ms, 5),
+        "first_region_ms": round(t["first_region_ms"], 5),
+        "regions": {"n": len(t["regions_ms"]), "launches_each": t["launches_per_region"],
+                    "ms_per_launch": [round(x, 5) for x in t["regions_ms"]],
+                    "value_is": "median of these regions (each >= --min-region-ms of back-to-back launches, taken "
+                                "after the clock has settled); first_region_ms is the region of exactly --steps "
+                                "launches right after --warmup"},
+        "wall_ms_per_step": round(t["wall_ms"], 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -280,14 +349,16 @@ def main():
                    "scale": "1/sqrt(d)", "inputs": "i.i.d. N(0,1), seeded, resident in HBM"},
         "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": None if args.causal else MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "traffic": None if prof is None else prof["bytes"],
+                     "traffic_source": None if prof is None else prof["profile"],
                      "algorithmic_flops_per_launch": flops, "algorithmic_hbm_bytes_per_launch": alg_bytes,
                      "kernel": "fa2_fwd_kernel", "kernel_ms": round(ms, 5),
+                     "kernel_ms_is": "HIP events on the launch stream around back-to-back launches, per launch "
+                                     "(one step = one launch of this kernel)",
+                     "secondary": {k: roofs[k] for k in ("alu_roof_tflops", "frac_alu_roof", "hbm_floor_ms",
+                                                          "frac_hbm_roof", "binding_roof")},
                      "mfma_roof_measured": roof,
                      "frac_of_measured_roof": None if roof is None else round(tflops / roof["normal_operands"]["tflops"], 4)},
-        "timing_regions": None if regions is None else {
-            "n": 5, "steps_each": args.steps, "best_ms": round(regions[0], 5), "median_ms": round(regions[2], 5),
-            "worst_ms": round(regions[4], 5)},
         "workloads": per_workload,
         "causal_same_shape": causal,
         "paper_context": "H100 PCIe, fp16: 295.7 TFLOP/s best at d=128 (Table 1), 39% of its 756 TFLOP/s peak; not a target",

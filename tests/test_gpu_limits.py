@@ -6,30 +6,15 @@ import pytest
 import oracle
 import paper_2312_11918_amd as fa2
 from paper_2312_11918_amd import workloads
+from _gpu_common import check, rows_one_per_tile, torch_gpu
 
 pytestmark = pytest.mark.gpu
 
-TOL_O_MAX, TOL_O_MEAN, TOL_LSE_MAX = 1e-2, 1e-3, 1e-3
-
-
-def _torch():
-    import torch
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    return torch
-
-
-def _check(o_gpu, lse_gpu, o_ref, lse_ref, what):
-    assert np.all(np.isfinite(o_gpu)) and np.all(np.isfinite(lse_gpu)), f"{what}: non-finite values"
-    eo = np.abs(o_gpu - o_ref)
-    el = np.abs(lse_gpu - lse_ref)
-    print(f"{what}: max|dO|={eo.max():.3e} mean|dO|={eo.mean():.3e} max|dLSE|={el.max():.3e}", flush=True)
-    assert eo.max() <= TOL_O_MAX and eo.mean() <= TOL_O_MEAN and el.max() <= TOL_LSE_MAX, what
-
 
 @pytest.mark.parametrize("causal", [False, True])
-def test_very_long_sequence_sampled(causal):
+def test_very_long_sequence_one_row_per_query_tile(causal):
     # N = 65536: 1024 K/V tiles per Q tile, 512 Q tiles per head
-    torch = _torch()
+    torch = torch_gpu()
     B, H, N, d = 1, 2, 65536, 64
     print(f"long sequence N={N} causal={causal}", flush=True)
     qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 65536)
@@ -37,13 +22,12 @@ def test_very_long_sequence_sampled(causal):
     o, lse = fa2.fa2_fwd(q, k, v, 0.125, causal=causal)
     torch.cuda.synchronize()
     o, lse = o.double().cpu().numpy(), lse.double().cpu().numpy()
-    r = np.random.Generator(np.random.PCG64(5))
-    n = 256
-    rows = np.stack([np.zeros(n, dtype=np.int64), r.integers(0, H, n), r.integers(0, N, n)], axis=1).astype(np.int32)
-    rows[0], rows[1], rows[2] = (0, 0, 0), (0, H - 1, N - 1), (0, 1, N - 129)
+    # one row in every 128-row query tile of both heads (1024 workgroups, or 512 pairs under the mask), plus corners
+    rows = rows_one_per_tile(B, H, N, 128, 5 + int(causal))
+    rows[2] = (0, 1, N - 129)
     qf, kf, vf = (oracle.widen(x, "fp16") for x in (qb, kb, vb))
     o_rows, lse_rows = oracle.attention_rows(qf, kf, vf, 0.125, rows, causal=causal)
-    _check(o[0, rows[:, 2], rows[:, 1], :], lse[0, rows[:, 1], rows[:, 2]], o_rows, lse_rows, f"N={N} causal={causal}")
+    check(o[0, rows[:, 2], rows[:, 1], :], lse[0, rows[:, 1], rows[:, 2]], o_rows, lse_rows, f"N={N} causal={causal}")
     assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
 
 
@@ -51,7 +35,7 @@ def test_very_long_sequence_sampled(causal):
 def test_batch_entry_just_under_4_gib_sampled_heads():
     # N * H * d * 2 bytes = 2^32 - 2^17: the last K/V rows of the last heads sit at byte offsets just below 2^32,
     # the largest the kernel's 32-bit buffer offsets reach (one more head is refused, checked below).
-    torch = _torch()
+    torch = torch_gpu()
     B, N, H, d, dtype = 1, 1024, 32767, 64, "bf16"
     base_h = 257
     print(f"large batch entry H={H} N={N} d={d}", flush=True)
@@ -77,7 +61,7 @@ def test_batch_entry_just_under_4_gib_sampled_heads():
     hidx = torch.from_numpy(heads).cuda()
     o_g = o[:, :, hidx].double().cpu().numpy()
     lse_g = lse[:, hidx].double().cpu().numpy()
-    _check(o_g, lse_g, o_ref, lse_ref, f"H={H} sampled heads")
+    check(o_g, lse_g, o_ref, lse_ref, f"H={H} sampled heads")
     # a coarse look at everything else: finite, and inside the range of V
     assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
     assert float(o.float().abs().max()) <= float(v.float().abs().max())

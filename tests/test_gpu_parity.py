@@ -8,44 +8,9 @@ import pytest
 import oracle
 import paper_2312_11918_amd as fa2
 from paper_2312_11918_amd import workloads
+from _gpu_common import TOL_LSE_MAX, TOL_O_MAX, check, rows_one_per_tile, run_gpu, to_device, torch_gpu
 
 pytestmark = pytest.mark.gpu
-
-TOL_O_MAX, TOL_O_MEAN, TOL_LSE_MAX = 1e-2, 1e-3, 1e-3
-
-
-def _torch():
-    import torch
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    return torch
-
-
-def _to_device(bits, dtype):
-    torch = _torch()
-    t = torch.from_numpy(bits.view(np.int16)).cuda()
-    return t.view(torch.float16 if dtype == "fp16" else torch.bfloat16)
-
-
-def _run_gpu(qb, kb, vb, dtype, scale, variant=0):
-    """Runs fa2_fwd and returns (O as fp64 numpy [B,N,H,d], LSE as fp64 numpy [B,H,N])."""
-    torch = _torch()
-    q, k, v = (_to_device(x, dtype) for x in (qb, kb, vb))
-    o = torch.full_like(q, float("nan"))
-    lse = torch.full((q.shape[0], q.shape[2], q.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
-    fa2.fa2_fwd(q, k, v, scale, out=o, lse=lse, variant=variant)
-    torch.cuda.synchronize()
-    return o.double().cpu().numpy(), lse.double().cpu().numpy()
-
-
-def _check(o_gpu, lse_gpu, o_ref, lse_ref, what):
-    assert np.all(np.isfinite(o_gpu)), f"{what}: O has non-finite values"
-    assert np.all(np.isfinite(lse_gpu)), f"{what}: LSE has non-finite values"
-    eo = np.abs(o_gpu - o_ref)
-    el = np.abs(lse_gpu - lse_ref)
-    print(f"{what}: max|dO|={eo.max():.3e} mean|dO|={eo.mean():.3e} max|dLSE|={el.max():.3e}", flush=True)
-    assert eo.max() <= TOL_O_MAX, f"{what}: max |dO| {eo.max():.3e}"
-    assert eo.mean() <= TOL_O_MEAN, f"{what}: mean |dO| {eo.mean():.3e}"
-    assert el.max() <= TOL_LSE_MAX, f"{what}: max |dLSE| {el.max():.3e}"
 
 
 # ------------------------------------------------------------------ element by element, small and medium shapes
@@ -67,8 +32,8 @@ def test_parity_elementwise(B, H, N, d, dtype):
     qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, seed)
     scale = float(np.float32(d) ** np.float32(-0.5))
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
-    o, lse = _run_gpu(qb, kb, vb, dtype, scale)
-    _check(o, lse, o_ref, lse_ref, f"B{B} H{H} N{N} d{d} {dtype}")
+    o, lse = run_gpu(qb, kb, vb, dtype, scale)
+    check(o, lse, o_ref, lse_ref, f"B{B} H{H} N{N} d{d} {dtype}")
 
 
 @pytest.mark.parametrize("variant", [fa2.FA2_VARIANT_NARROW, fa2.FA2_VARIANT_WIDE, fa2.FA2_VARIANT_NARROW8,
@@ -88,16 +53,16 @@ def test_parity_explicit_variants(B, H, N, d, dtype, variant):
     qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, seed, k_outlier_frac=frac, k_outlier_gain=6.0)
     scale = float(np.float32(d) ** np.float32(-0.5))
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
-    o, lse = _run_gpu(qb, kb, vb, dtype, scale, variant)
-    _check(o, lse, o_ref, lse_ref, f"variant {variant} B{B} H{H} N{N} d{d} {dtype}")
+    o, lse = run_gpu(qb, kb, vb, dtype, scale, variant)
+    check(o, lse, o_ref, lse_ref, f"variant {variant} B{B} H{H} N{N} d{d} {dtype}")
 
 
 def test_parity_workload_1_full():
     w, qb, kb, vb = workloads.make_workload(1)
     print(f"workload 1 {w.name} seed={w.seed}", flush=True)
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, w.dtype) for x in (qb, kb, vb)), w.scale)
-    o, lse = _run_gpu(qb, kb, vb, w.dtype, w.scale)
-    _check(o, lse, o_ref, lse_ref, w.name)
+    o, lse = run_gpu(qb, kb, vb, w.dtype, w.scale)
+    check(o, lse, o_ref, lse_ref, w.name)
 
 
 def test_parity_outlier_keys_medium():
@@ -107,75 +72,70 @@ def test_parity_outlier_keys_medium():
     qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 4242, k_outlier_frac=0.01, k_outlier_gain=8.0)
     scale = 0.125
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), scale)
-    o, lse = _run_gpu(qb, kb, vb, "fp16", scale)
-    _check(o, lse, o_ref, lse_ref, "outliers N2048 d64")
+    o, lse = run_gpu(qb, kb, vb, "fp16", scale)
+    check(o, lse, o_ref, lse_ref, "outliers N2048 d64")
 
 
-def test_parity_paper_shape_d256_sampled():
-    # the paper's d = 256 benchmark shape (Section 7: batch 4, N = 4096, 8 heads x 256), sampled rows
-    B, H, N, d = 4, 8, 4096, 256
-    print("paper shape d256", flush=True)
-    qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 256256)
-    scale = 1.0 / 16.0
-    o, lse = _run_gpu(qb, kb, vb, "fp16", scale)
+# The paper's own benchmark shapes (Section 7, caption of the last figure: SEQLEN = KEYLEN = 4096, batch 4,
+# heads x head_dim = 32x64, 16x128, 8x256; fp16, N(0,1)).
+PAPER_SHAPES = {64: (4, 32, 4096, 64), 128: (4, 16, 4096, 128), 256: (4, 8, 4096, 256)}
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_parity_paper_shapes_whole_output(d):
+    # default tile shape, every element of O and LSE against Algorithm 1 in fp64
+    B, H, N, _ = PAPER_SHAPES[d]
+    seed = 4096000 + d
+    print(f"paper shape B={B} H={H} N={N} d={d} fp16 seed={seed}", flush=True)
+    qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", seed)
+    scale = float(np.float32(d) ** np.float32(-0.5))
+    o, lse = run_gpu(qb, kb, vb, "fp16", scale)
+    o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), scale)
+    check(o, lse, o_ref, lse_ref, f"paper shape B{B} H{H} N{N} d{d} fp16 (whole output)")
+
+
+@pytest.mark.parametrize("variant", [fa2.FA2_VARIANT_NARROW8])
+@pytest.mark.parametrize("d", [64, 128])
+def test_parity_paper_shapes_sweep_variants(d, variant):
+    # the other tile shape of the sweep on the paper's shapes: one sampled row in every 128-row query tile of every
+    # head (4096 rows of the 524288 / 262144), against the oracle row by row
+    B, H, N, _ = PAPER_SHAPES[d]
+    seed = 4096000 + d
+    print(f"paper shape variant {variant} B={B} H={H} N={N} d={d} fp16 seed={seed}", flush=True)
+    qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", seed)
+    scale = float(np.float32(d) ** np.float32(-0.5))
+    o, lse = run_gpu(qb, kb, vb, "fp16", scale, variant)
     assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
-    r = np.random.Generator(np.random.PCG64(31))
-    n = 512
-    rows = np.stack([r.integers(0, B, n), r.integers(0, H, n), r.integers(0, N, n)], axis=1).astype(np.int32)
-    rows[0], rows[1] = (0, 0, 0), (B - 1, H - 1, N - 1)
+    rows = rows_one_per_tile(B, H, N, 128, 500 + d + variant)
     q, k, v = (oracle.widen(x, "fp16") for x in (qb, kb, vb))
     o_rows, lse_rows = oracle.attention_rows(q, k, v, scale, rows)
-    _check(o[rows[:, 0], rows[:, 2], rows[:, 1], :], lse[rows[:, 0], rows[:, 1], rows[:, 2]], o_rows, lse_rows,
-           "paper shape B4 H8 N4096 d256 (512 sampled rows)")
+    check(o[rows[:, 0], rows[:, 2], rows[:, 1], :], lse[rows[:, 0], rows[:, 1], rows[:, 2]], o_rows, lse_rows,
+          f"paper shape d{d} variant {variant} ({len(rows)} rows, one per query tile)")
 
 
-# ------------------------------------------------------------------ full-size workloads: sampled rows + whole heads
-def _sample_rows(w, n, seed):
-    r = np.random.Generator(np.random.PCG64(seed))
-    rows = np.stack([r.integers(0, w.B, n), r.integers(0, w.H, n), r.integers(0, w.N, n)], axis=1).astype(np.int32)
-    # always include the corners: first/last batch, head, row
-    rows[0] = (0, 0, 0)
-    rows[1] = (w.B - 1, w.H - 1, w.N - 1)
-    rows[2] = (0, w.H - 1, 127)
-    rows[3] = (w.B - 1, 0, 128)
-    return rows
-
-
-@pytest.mark.parametrize("index,n_rows,full_heads", [(2, 2048, 4), (3, 1024, 2), (4, 512, 0), (5, 512, 0)])
-def test_parity_full_size_workloads(index, n_rows, full_heads):
+# ------------------------------------------------------------------ the full-size workloads, every element
+@pytest.mark.parametrize("index", [2, 3, 4, 5])
+def test_parity_full_size_workloads(index):
+    # Algorithm 1 in fp64 over the whole workload, in the launch configuration bench.py times: every element of O
+    # and LSE of every workgroup is compared (the oracle takes seconds to half a minute per workload)
     w, qb, kb, vb = workloads.make_workload(index)
     print(f"workload {index} {w.name} seed={w.seed}", flush=True)
-    o, lse = _run_gpu(qb, kb, vb, w.dtype, w.scale)
-    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+    o, lse = run_gpu(qb, kb, vb, w.dtype, w.scale)
     q, k, v = (oracle.widen(x, w.dtype) for x in (qb, kb, vb))
-    rows = _sample_rows(w, n_rows, 77 + index)
-    o_rows, lse_rows = oracle.attention_rows(q, k, v, w.scale, rows)
-    o_g = o[rows[:, 0], rows[:, 2], rows[:, 1], :]
-    lse_g = lse[rows[:, 0], rows[:, 1], rows[:, 2]]
-    _check(o_g, lse_g, o_rows, lse_rows, f"{w.name} ({n_rows} sampled rows)")
-    r = np.random.Generator(np.random.PCG64(99 + index))
-    for _ in range(full_heads):
-        b, h = int(r.integers(0, w.B)), int(r.integers(0, w.H))
-        sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
-        o_ref, lse_ref = oracle.attention(q[sl], k[sl], v[sl], w.scale)
-        _check(o[sl], lse[b:b + 1, h:h + 1], o_ref, lse_ref, f"{w.name} head b={b} h={h}")
-    # a property that holds at any size: every output row is a convex combination of value rows
-    vmax = v.max(axis=1)[:, None]      # [B,1,H,d]
-    vmin = v.min(axis=1)[:, None]
-    slack = 2e-2
-    assert np.all(o <= vmax + slack) and np.all(o >= vmin - slack)
+    o_ref, lse_ref = oracle.attention(q, k, v, w.scale)
+    check(o, lse, o_ref, lse_ref, f"{w.name} (whole output)")
 
 
 # ------------------------------------------------------------------ metamorphic checks on the GPU path
 def test_constant_V_and_identical_keys():
-    torch = _torch()
+    torch = torch_gpu()
     B, H, N, d = 1, 2, 512, 128
     qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 31)
     q = oracle.widen(qb, "fp16")
     # identical keys and values: O = V_0 exactly representable, LSE = s_0 + ln N
     kb2 = np.broadcast_to(kb[:, :1], kb.shape).copy()
     vb2 = np.broadcast_to(vb[:, :1], vb.shape).copy()
-    o, lse = _run_gpu(qb, kb2, vb2, "fp16", 0.0883883461356163)
+    o, lse = run_gpu(qb, kb2, vb2, "fp16", 0.0883883461356163)
     v0 = oracle.widen(vb2, "fp16")[:, :1]
     assert np.abs(o - v0).max() <= 2e-3
     s0 = 0.0883883461356163 * np.einsum("bihc,bhc->bhi", q, oracle.widen(kb2, "fp16")[:, 0])
@@ -186,8 +146,8 @@ def test_key_permutation_changes_nothing_beyond_rounding():
     B, H, N, d = 1, 2, 1024, 64
     qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 32, k_outlier_frac=0.02, k_outlier_gain=6.0)
     perm = np.random.Generator(np.random.PCG64(5)).permutation(N)
-    o0, l0 = _run_gpu(qb, kb, vb, "fp16", 0.125)
-    o1, l1 = _run_gpu(qb, kb[:, perm].copy(), vb[:, perm].copy(), "fp16", 0.125)
+    o0, l0 = run_gpu(qb, kb, vb, "fp16", 0.125)
+    o1, l1 = run_gpu(qb, kb[:, perm].copy(), vb[:, perm].copy(), "fp16", 0.125)
     assert np.abs(o1 - o0).max() <= 5e-3
     assert np.abs(l1 - l0).max() <= 1e-4
 
@@ -203,20 +163,20 @@ def test_split_key_merge_through_LSE():
     va = np.concatenate([vb[:, :half], vb[:, :half]], axis=1)
     kc = np.concatenate([kb[:, half:], kb[:, half:]], axis=1)
     vc = np.concatenate([vb[:, half:], vb[:, half:]], axis=1)
-    oa, la = _run_gpu(qb, ka, va, "fp16", 0.125)
-    oc, lc = _run_gpu(qb, kc, vc, "fp16", 0.125)
+    oa, la = run_gpu(qb, ka, va, "fp16", 0.125)
+    oc, lc = run_gpu(qb, kc, vc, "fp16", 0.125)
     la, lc = la - np.log(2.0), lc - np.log(2.0)
     lm = np.logaddexp(la, lc)
     wa = np.exp(la - lm).transpose(0, 2, 1)[..., None]
     wc = np.exp(lc - lm).transpose(0, 2, 1)[..., None]
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), 0.125)
-    _check(wa * oa + wc * oc, lm, o_ref, lse_ref, "split-key merge")
+    check(wa * oa + wc * oc, lm, o_ref, lse_ref, "split-key merge")
 
 
 def test_lse_may_be_null_and_outputs_untouched_on_error():
-    torch = _torch()
+    torch = torch_gpu()
     qb, kb, vb = workloads.make_qkv(1, 128, 2, 64, "fp16", 34)
-    q, k, v = (_to_device(x, "fp16") for x in (qb, kb, vb))
+    q, k, v = (to_device(x, "fp16") for x in (qb, kb, vb))
     o1, _ = fa2.fa2_fwd(q, k, v, 0.125, return_lse=False)
     o2, lse = fa2.fa2_fwd(q, k, v, 0.125)
     torch.cuda.synchronize()
@@ -228,9 +188,9 @@ def test_lse_may_be_null_and_outputs_untouched_on_error():
 
 
 def test_runs_on_a_side_stream_and_is_deterministic():
-    torch = _torch()
+    torch = torch_gpu()
     qb, kb, vb = workloads.make_qkv(2, 256, 2, 128, "bf16", 35)
-    q, k, v = (_to_device(x, "bf16") for x in (qb, kb, vb))
+    q, k, v = (to_device(x, "bf16") for x in (qb, kb, vb))
     o0, l0 = fa2.fa2_fwd(q, k, v, 0.09)
     s = torch.cuda.Stream()
     s.wait_stream(torch.cuda.current_stream())
@@ -244,7 +204,7 @@ def test_runs_on_a_side_stream_and_is_deterministic():
 def test_launch_can_be_captured_in_a_hip_graph_and_replayed():
     # fa2_fwd only enqueues a kernel, so a stream capture records it; every replay must equal an eager launch on
     # the inputs that are in the buffers at that time.  (Nothing but the kernel is captured: no memset, no copy.)
-    torch = _torch()
+    torch = torch_gpu()
     B, H, N, d = 2, 3, 384, 128
     print("graph capture and replay", flush=True)
     q, k, v = (torch.empty((B, N, H, d), dtype=torch.float16, device="cuda") for _ in range(3))
@@ -254,7 +214,7 @@ def test_launch_can_be_captured_in_a_hip_graph_and_replayed():
     def fill(seed):
         qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", seed)
         for t, x in ((q, qb), (k, kb), (v, vb)):
-            t.copy_(_to_device(x, "fp16"))
+            t.copy_(to_device(x, "fp16"))
         return qb, kb, vb
 
     fill(50)
@@ -271,7 +231,7 @@ def test_launch_can_be_captured_in_a_hip_graph_and_replayed():
         torch.cuda.synchronize()
         assert torch.equal(o, o_eager) and torch.equal(lse, lse_eager), f"replay with seed {seed} differs from eager"
         o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), 0.1, causal=True)
-        _check(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, f"graph replay seed {seed}")
+        check(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, f"graph replay seed {seed}")
 
 
 @pytest.mark.parametrize("scale", [1e-3, 0.5, 4.0])
@@ -282,7 +242,7 @@ def test_parity_over_softmax_scales(scale, dtype):
     print(f"scale {scale} {dtype}", flush=True)
     qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, 61)
     o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
-    o, lse = _run_gpu(qb, kb, vb, dtype, scale)
+    o, lse = run_gpu(qb, kb, vb, dtype, scale)
     if dtype == "bf16" and scale >= 0.5:
         # A peaked P reproduces a few V rows: outputs beyond 2.56 in magnitude, where half an ulp of the bf16 output
         # alone is up to |O| * 2^-8, and the bf16 rounding of the few dominant P~ (relative 2^-9 each, Section 4.2's
@@ -290,12 +250,12 @@ def test_parity_over_softmax_scales(scale, dtype):
         assert np.all(np.abs(o - o_ref) <= np.maximum(TOL_O_MAX, np.abs(o_ref) * 2.0 ** -7))
         assert np.max(np.abs(lse - lse_ref)) <= TOL_LSE_MAX
     else:
-        _check(o, lse, o_ref, lse_ref, f"scale {scale} {dtype}")
+        check(o, lse, o_ref, lse_ref, f"scale {scale} {dtype}")
 
 
 def test_mfma_roof_probe_reports_a_plausible_clock_and_rate():
     # the measurement aid of bench.py: MFMA-only launch on supplied operands, engine clock from two counters
-    torch = _torch()
+    torch = torch_gpu()
     print("mfma roof probe", flush=True)
     n16 = fa2.FA2_PROBE_OPERAND_BYTES // 2
     vals = np.random.Generator(np.random.PCG64(3)).standard_normal(n16, dtype=np.float32)
@@ -324,14 +284,14 @@ def test_concurrent_launches_from_threads_on_their_own_streams():
     # the library keeps no state: launches from several host threads, each on a stream of its own, must give the
     # bits of the same launches made one after the other
     import threading
-    torch = _torch()
+    torch = torch_gpu()
     print("concurrent launches", flush=True)
     shapes = [(2, 3, 512, 128, "fp16", False), (1, 4, 1000, 64, "bf16", False), (2, 2, 640, 128, "fp16", True),
               (1, 2, 768, 256, "fp16", False)]
     jobs = []
     for i, (B, H, N, d, dtype, causal) in enumerate(shapes):
         qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, 700 + i)
-        q, k, v = (_to_device(x, dtype) for x in (qb, kb, vb))
+        q, k, v = (to_device(x, dtype) for x in (qb, kb, vb))
         o_seq, lse_seq = fa2.fa2_fwd(q, k, v, 0.1, causal=causal)
         jobs.append((q, k, v, causal, o_seq, lse_seq))
     torch.cuda.synchronize()

@@ -6,23 +6,17 @@ import pytest
 import oracle
 import paper_2312_11918_amd as fa2
 from paper_2312_11918_amd import workloads
+from _gpu_common import check, torch_gpu
 
 pytestmark = pytest.mark.gpu
 
-TOL_O_MAX, TOL_O_MEAN, TOL_LSE_MAX = 1e-2, 1e-3, 1e-3
 SENT16, SENT32 = 0x7E00, np.float32(-12345.0)  # fp16/bf16 NaN pattern as a sentinel; LSE sentinel
 PAD = 4096  # sentinel elements on each side of every device tensor
 
 
-def _torch():
-    import torch
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    return torch
-
-
 def _guarded(bits, dtype):
     """Device tensor holding `bits` with PAD NaN-pattern elements before and after it; returns (view, whole)."""
-    torch = _torch()
+    torch = torch_gpu()
     flat = np.full(bits.size + 2 * PAD, SENT16, dtype=np.uint16)
     flat[PAD:PAD + bits.size] = bits.reshape(-1)
     whole = torch.from_numpy(flat.view(np.int16)).cuda()
@@ -38,7 +32,7 @@ def _make(B, H, Nq, Nk, d, dtype, seed, outliers=0.0):
 
 def _run(qb, kb, vb, dtype, scale, causal=False):
     """Runs the library on guarded buffers; checks that no sentinel moved and nothing outside Q, K, V leaked in."""
-    torch = _torch()
+    torch = torch_gpu()
     B, Nq, H, d = qb.shape
     q, _ = _guarded(qb, dtype)
     k, _ = _guarded(kb, dtype)
@@ -56,14 +50,8 @@ def _run(qb, kb, vb, dtype, scale, causal=False):
 
 
 def _check(o_gpu, lse_gpu, o_ref, lse_ref, what):
-    assert np.all(np.isfinite(o_gpu)), f"{what}: O has non-finite values (unwritten rows or leaked padding)"
-    assert np.all(np.isfinite(lse_gpu)) and not np.any(lse_gpu == SENT32), f"{what}: LSE has unwritten entries"
-    eo = np.abs(o_gpu - o_ref)
-    el = np.abs(lse_gpu - lse_ref)
-    print(f"{what}: max|dO|={eo.max():.3e} mean|dO|={eo.mean():.3e} max|dLSE|={el.max():.3e}", flush=True)
-    assert eo.max() <= TOL_O_MAX, f"{what}: max |dO| {eo.max():.3e}"
-    assert eo.mean() <= TOL_O_MEAN, f"{what}: mean |dO| {eo.mean():.3e}"
-    assert el.max() <= TOL_LSE_MAX, f"{what}: max |dLSE| {el.max():.3e}"
+    assert not np.any(lse_gpu == SENT32), f"{what}: LSE has unwritten entries"
+    check(o_gpu, lse_gpu, o_ref, lse_ref, what)   # non-finite values: unwritten rows or leaked padding
 
 
 @pytest.mark.parametrize("B,H,Nq,Nk,d,dtype,causal,outliers", [
@@ -97,29 +85,21 @@ def test_ragged_parity_elementwise(B, H, Nq, Nk, d, dtype, causal, outliers):
 
 
 @pytest.mark.parametrize("N,causal", [(2047, False), (2049, False), (2000, True)])
-def test_ragged_headline_shape_sampled(N, causal):
-    # the headline shape with a length that is not a whole number of tiles, sampled rows
+def test_ragged_headline_shape_whole_output(N, causal):
+    # the headline shape with a length that is not a whole number of tiles: every element against the oracle
     B, H, d = 8, 16, 128
     print(f"ragged headline N={N} causal={causal}", flush=True)
     qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 9000 + N)
     scale = float(np.float32(d) ** np.float32(-0.5))
     o, lse = _run(qb, kb, vb, "fp16", scale, causal)
-    r = np.random.Generator(np.random.PCG64(N))
-    n = 768
-    rows = np.stack([r.integers(0, B, n), r.integers(0, H, n), r.integers(0, N, n)], axis=1).astype(np.int32)
-    rows[0], rows[1], rows[2] = (0, 0, 0), (B - 1, H - 1, N - 1), (3, 5, N - 2)
-    rows[3:40, 2] = N - 1 - np.arange(37)   # the rows of the last, partial Q tile
-    q, k, v = (oracle.widen(x, "fp16") for x in (qb, kb, vb))
-    o_rows, lse_rows = oracle.attention_rows(q, k, v, scale, rows, causal=causal)
-    _check(o[rows[:, 0], rows[:, 2], rows[:, 1], :], lse[rows[:, 0], rows[:, 1], rows[:, 2]], o_rows, lse_rows,
-           f"B8 H16 N{N} d128 causal={causal} ({n} sampled rows)")
-    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+    o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), scale, causal=causal)
+    _check(o, lse, o_ref, lse_ref, f"B8 H16 N{N} d128 causal={causal} (whole output)")
 
 
 def test_keys_past_the_end_are_invisible_bitwise():
     # Nq x Nk attention must not depend on what follows K and V in memory: running on the first Nk rows of a longer,
     # different K/V (as its own contiguous tensor) and on guarded buffers gives the same bits as any other padding.
-    torch = _torch()
+    torch = torch_gpu()
     B, H, Nq, Nk, d = 1, 2, 150, 90, 128
     print("keys past the end", flush=True)
     qb, kb, vb = _make(B, H, Nq, Nk, d, "fp16", 4321)
