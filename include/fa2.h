@@ -73,14 +73,11 @@ int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, in
 /* Tile shapes (the counterpart of the paper's QBLK x KBLK choice, Section 7 and Table 1). */
 enum {
   FA2_VARIANT_AUTO = 0,   /* pick by problem shape (what fa2_fwd does)                                  */
-  FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (32 per wavefront), 2 workgroups per CU       */
-  FA2_VARIANT_WIDE = 2,   /* 256 query rows per workgroup (4 wavefronts x 64 rows), 1 workgroup per CU;
-                             needs N to be a multiple of 256 and d <= 128                               */
-  FA2_VARIANT_NARROW8 = 3,/* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
-                             K/V loaded three tiles ahead; needs N to be a multiple of 256 and d <= 128 */
-  FA2_VARIANT_PIPE = 4    /* the NARROW shape with the softmax of 32 keys interleaved, instruction by
-                             instruction, with the MFMAs of the neighbouring 32-key stages; needs N to
-                             be a multiple of 128 and d <= 128                                          */
+  FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (4 wavefronts x 32 rows), 2 workgroups per CU,
+                             K/V tiles of 64 keys double-buffered in LDS                                */
+  FA2_VARIANT_NARROW8 = 3 /* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
+                             K/V loaded three tiles ahead, half the L2 -> LDS traffic per FLOP; needs N
+                             to be a multiple of 256 and d <= 128                                       */
 };
 
 /*

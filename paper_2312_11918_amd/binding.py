@@ -16,9 +16,7 @@ FA2_ERR_UNSUPPORTED = -2
 FA2_ERR_LAUNCH = -3
 FA2_VARIANT_AUTO = 0
 FA2_VARIANT_NARROW = 1
-FA2_VARIANT_WIDE = 2
 FA2_VARIANT_NARROW8 = 3
-FA2_VARIANT_PIPE = 4
 FA2_MASK_NONE = 0
 FA2_MASK_CAUSAL = 1
 

@@ -153,12 +153,7 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 // the last row (finite data) and their columns of S are set to -inf in the last kNBuf tiles, the only ones
 // that can hold them; the tile count is rounded up to a multiple of kNBuf (a padding tile is fully masked).
 //
-// kPipe selects a software pipeline inside the wavefront, over STAGES of 32 keys (half a K/V tile):
-//     stage s:   matrix cores:  O += P~_{s-1} V_{s-1}   and   S_{s+1} = K_{s+1} Q^T, MFMAs alternating
-//                vector ALU:    online softmax of S_s -> P~_s, cut into chunks that follow the MFMAs one by one
-// so that every wavefront offers work for both pipes all the time, instead of a block of softmax followed by a
-// block of MFMAs that has to meet the opposite block of the other wavefront on its SIMD.
-template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged, bool kPipe = false>
+template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
 __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_fwd_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ LSE, int H, int Nq, int Nk, float scale_log2e, int n_qtiles,
@@ -170,7 +165,6 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   static_assert(kNBuf == 2 || kNBuf == 4, "two or four LDS buffers per operand");
   constexpr int kRows = 32 * kWv;   // query rows per workgroup
   static_assert(kRows == kNBuf * kBc, "a Q tile spans exactly kNBuf K/V tiles (the causal tile count relies on it)");
-  static_assert(!kPipe || kNBuf == 2, "the stage pipeline is written for two LDS buffers per operand");
   constexpr int kKSteps = D / 16;   // MFMA steps along d for S^T = K Q^T
   constexpr int kDBlocks = D / 32;  // 32-row blocks of O^T
   constexpr int kKBlocks = kBc / 32;  // 32-key blocks of S^T
@@ -179,6 +173,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   constexpr int kSteps2 = kTSteps * kDBlocks;  // MFMAs of GEMM-II per tile
   constexpr int kRing = 4;                     // operand fragments in flight between LDS and the MFMAs
   constexpr int kLoadsPerWave = T::kElems * 2 / 1024 / kWv;  // 1 KiB wavefront loads per tile and wavefront
+  constexpr bool kSplitRefill = kNBuf == 2 && D == 256;    // K and V refills issued as two separate bursts
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
   // buffer cannot alias the operand reads from another.  (With kNBuf == 2 the last two pairs are unused.)
@@ -242,6 +237,10 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // is_k is a compile-time tag: K and V tiles use different chunk swizzles.  The per-lane source offsets are
   // recomputed at every call (a few integer operations per tile) instead of being kept in registers.
   auto stage_in = [&](auto is_k, __amdgpu_buffer_rsrc_t rsrc, int j, uint16_t* lds_tile) __attribute__((always_inline)) {
+    int lane = tid & 63;
+    // d = 256 with partial tiles has no registers to spare for sixteen loop-invariant source offsets: keep them
+    // from being hoisted out of the loop (they cost a few integer operations per load to recompute)
+    if constexpr (D == 256 && kRagged) asm volatile("" : "+v"(lane));
     if (kRagged && (j + 1) * kBc > Nk) {
       // a tile with rows past the last key: those rows are filled with copies of the last key's row, so LDS
       // holds finite numbers everywhere (their columns of S are masked; 0 * finite = 0 in GEMM-II)
@@ -269,9 +268,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   };
 
   // Per-lane LDS element offsets of the operand reads (row part + swizzled chunk part).
-  int k_addr[kKSteps];  // K fragment of MFMA step ks: row r (+32 per key block), chunk 2 ks + hh
+  // K fragment of MFMA step ks: row r (+32 per key block), chunk 2 ks + hh.  The swizzle only touches the low four
+  // bits of the chunk index, so steps 8 apart (d = 256) differ by a constant 16 chunks and share one register.
+  constexpr int kKAddrs = kKSteps < 8 ? kKSteps : 8;
+  int k_addr[kKAddrs];
 #pragma unroll
-  for (int ks = 0; ks < kKSteps; ++ks) k_addr[ks] = r * D + 8 * ((2 * ks + hh) ^ T::swz_k(r));
+  for (int ks = 0; ks < kKAddrs; ++ks) k_addr[ks] = r * D + 8 * ((2 * ks + hh) ^ T::swz_k(r));
   int v_addr[kDBlocks];  // V fragment of d-block db: row 4 hh + (lane%16)/4 (+16 per step, +8 for the upper half)
   {
     const int l16 = lane & 15;
@@ -286,10 +288,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Accumulators of Algorithm 2: O^T (fp32), the rowmax reference and the running rowsum.  Each half
   // of the wavefront keeps the partial rowsum of its own keys; the two are added in the epilogue.
   f32x16 ot[kDBlocks];
-  f32x16 st[kKBlocks];  // S^T of the tile being processed; stage pipeline: st[s % 2] is S^T of stage s
-  u32x4 pbuf[2][2];          // stage pipeline only: P~ of stages s-1 and s (two 16-key MFMA steps each)
-  float alpha_pend = 1.f;    // stage pipeline only: rescale of O decided by the last softmax, not yet applied
-  bool rescale_pend = false;
+  f32x16 st[kKBlocks];  // S^T of the tile being processed
   float m_ref;          // reference point of the exponentials, in units of the unscaled logits q.k
   float mc_ref;         // m_ref * scale * log2(e)
   float l_run;
@@ -297,7 +296,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Operand fragment of MFMA step `step` of GEMM-I (K rows) / GEMM-II (V columns, transposed by the load).
   auto k_frag = [&](const uint16_t* kt, int step) __attribute__((always_inline)) -> u32x4 {
     const int ks = step / kKBlocks, kb = step % kKBlocks;
-    return *reinterpret_cast<const u32x4*>(kt + k_addr[ks] + kb * 32 * D);
+    return *reinterpret_cast<const u32x4*>(kt + k_addr[ks % kKAddrs] + (ks / kKAddrs) * 128 + kb * 32 * D);
   };
   auto v_frag = [&](const uint16_t* vt, int step) __attribute__((always_inline)) -> u32x4 {
     const int t = step / kDBlocks, db = step % kDBlocks;
@@ -332,8 +331,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // mask_tag: the tile straddles the causal diagonal; `visible` is then the largest value of
   // 32 kb + 8 (v/4) + v%4 (the key's position in the tile minus this half's 4 hh) that register v of key
   // block kb may have for its key to be at or before this lane's query.
-  auto iteration = [&](auto next_tag, auto mask_tag, int visible, const uint16_t* v_cur,
-                       const uint16_t* k_next) __attribute__((always_inline)) {
+  auto iteration = [&](auto next_tag, auto mask_tag, int visible, const uint16_t* v_cur, const uint16_t* k_next,
+                       int jj, uint16_t* k_refill) __attribute__((always_inline)) {
     if constexpr (decltype(mask_tag)::value) {
       // S_ij = -inf for j > i: the exponential below turns it into an exact 0 in P~ and in the rowsum.  Key 0
       // is visible to every query, so the reference point is finite from the first tile on.
@@ -344,59 +343,120 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
           if (32 * kb + 8 * (v / 4) + (v % 4) > visible) st[kb][v] = -INFINITY;
     }
     // ---- online softmax for this lane's query (Algorithm 2: rowmax, P~, rowsum, rescale) ----
-    // The maximum is taken on the unscaled logits (valid for scale > 0) and the scale is folded into
-    // the exponent: exp(scale*(s - m)) = exp2(s*c - m*c) with c = scale*log2(e).
+    // The scale is folded into the exponent, exp(scale*(s - m)) = exp2(s*c - m*c) with c = scale*log2(e), and
+    // the maximum is taken on the unscaled logits (valid for scale > 0).
+    //
+    // The reference point m of the exponentials only has to keep them in range, it need not be the running
+    // maximum of Algorithm 2: the result is unchanged because the reference cancels in O / l.  It is moved (and
+    // O, l rescaled by exp(m_old - m_new)) only when a tile would otherwise produce a P~ above 2^kLazyLog2.
     __builtin_amdgcn_s_setprio(0);
-    float mx = max2_raw(st[0][0], st[0][1]);
-#pragma unroll
-    for (int kb = 0; kb < kKBlocks; ++kb)
-#pragma unroll
-      for (int v = (kb == 0 ? 2 : 0); v < 16; v += 2) mx = max3_raw(mx, st[kb][v], st[kb][v + 1]);
-    mx = max_with_partner_half_raw(mx);
-    // The reference point only has to keep the exponentials in range, it need not be the exact
-    // running maximum: it is moved (and O, l rescaled by exp(m_old - m_new)) only when the tile maximum
-    // exceeds it by more than 2^kLazyLog2; until then P~ <= 2^kLazyLog2.  The result is unchanged
-    // because the reference cancels in O / l; on the first tile m_ref = -inf forces the move.
-    const bool move = (mx - m_ref) * scale_log2e > kLazyLog2;
-    if (__builtin_amdgcn_ballot_w64(move) != 0) {
-      const float m_new = move ? mx : m_ref;
-      const float mc_new = m_new * scale_log2e;
-      // exp(m_old - m_new); 0 on the first tile.  A lane whose own row does not move (the branch is taken when
-      // any lane of the wavefront moves) gets exactly 1, not exp2 of a contracted m*c - m*c that may differ from
-      // 0 in the last bit: a row's result must not depend on what other rows of the wavefront see.
-      const float alpha = move ? __builtin_amdgcn_exp2f(mc_ref - mc_new) : 1.0f;
-      m_ref = m_new;
-      mc_ref = mc_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
-    }
+    constexpr bool kMasked = decltype(mask_tag)::value;
+    constexpr float kLazyLimit = 256.0f;  // 2^kLazyLog2
+    // d = 256 takes the maximum on every tile and skips the rescale when no row of the wavefront moves; the lazy
+    // path reaches update_reference only when some row does (or on first and masked tiles)
+    constexpr bool kSkipIdleRescale = D == 256;
+    static_assert(kLazyLog2 == 8.0f, "kLazyLimit is 2^kLazyLog2");
+    u32x4 ring[kRing];   // operand fragments on their way from LDS to the MFMAs
+    float rowsum[2];
+    u32x4 pf[kTSteps];
 
-    // first V fragments: independent of P~, so their LDS latency hides behind the exponentials
-    u32x4 ring[kRing];
+    // Row maximum of this tile (both halves of the wavefront), the move of the reference point for the rows that
+    // `moves(mx)` selects, and the rescale of l and O.
+    auto update_reference = [&](auto moves) __attribute__((always_inline)) {
+      float mx = max2_raw(st[0][0], st[0][1]);
 #pragma unroll
-    for (int i = 0; i < kRing; ++i) ring[i] = v_frag(v_cur, i);
-
+      for (int kb = 0; kb < kKBlocks; ++kb)
+#pragma unroll
+        for (int v = (kb == 0 ? 2 : 0); v < 16; v += 2) mx = max3_raw(mx, st[kb][v], st[kb][v + 1]);
+      mx = max_with_partner_half_raw(mx);
+      const bool move = moves(mx);
+      if (!kSkipIdleRescale || __builtin_amdgcn_ballot_w64(move) != 0) {
+        const float m_new = move ? mx : m_ref;
+        const float mc_new = m_new * scale_log2e;
+        // exp(m_old - m_new); 0 on the first tile.  A row that stays (the branch is taken when any row of the
+        // wavefront moves) gets exactly 1, not exp2 of a contracted m*c - m*c that may differ from 0 in the last
+        // bit: a row's result must not depend on what the other rows of the wavefront hold.
+        const float alpha = move ? __builtin_amdgcn_exp2f(mc_ref - mc_new) : 1.0f;
+        m_ref = m_new;
+        mc_ref = mc_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) ot[db][v] *= alpha;
+      }
+    };
+    // Issued once per tile, right before its first round of exponentials:
+    //  * the second half of the refill (kSplitRefill): K tile jj + kNBuf into the buffer that held K tile jj, which
+    //    every wavefront finished reading before the barrier that precedes this iteration.  The V half was issued
+    //    right after that barrier.  At d = 256 a tile pair is 16 loads per wavefront; issued as one burst they
+    //    overrun the queue between the wavefronts and the texture unit, which accepts about four loads per
+    //    wavefront at once and then only as fast as the path into LDS drains, and every wavefront of the workgroup
+    //    stands still meanwhile;
+    //  * the first V fragments of GEMM-II: independent of P~, so their LDS latency hides behind the exponentials.
+    auto stage_ahead = [&]() __attribute__((always_inline)) {
+      if constexpr (kSplitRefill) {
+        if (jj + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, jj + kNBuf, k_refill);
+      }
+#pragma unroll
+      for (int i = 0; i < kRing; ++i) ring[i] = v_frag(v_cur, i);
+    };
     // P~ = exp2(s*c - m*c): the rowsum is taken in fp32 from the unrounded values (Algorithm 2 keeps it in
     // the accumulator type); rounded to 16 bit, registers 8t..8t+7 of a 32-key block are the 8 B-operand
     // slots of MFMA step t.
-    float rowsum[2] = {0.f, 0.f};
-    u32x4 pf[kTSteps];
+    auto exponentials = [&]() __attribute__((always_inline)) {
+      rowsum[0] = 0.f;
+      rowsum[1] = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < kKBlocks; ++kb) {
+      for (int kb = 0; kb < kKBlocks; ++kb) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < 2; ++t) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int v = 8 * t + 2 * c;
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][v], scale_log2e, -mc_ref));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][v + 1], scale_log2e, -mc_ref));
-          rowsum[0] += p0;
-          rowsum[1] += p1;
-          pf[kb * 2 + t][c] = E::pack2(p0, p1);
+          for (int c = 0; c < 4; ++c) {
+            const int v = 8 * t + 2 * c;
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][v], scale_log2e, -mc_ref));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][v + 1], scale_log2e, -mc_ref));
+            rowsum[0] += p0;
+            rowsum[1] += p1;
+            pf[kb * 2 + t][c] = E::pack2(p0, p1);
+          }
         }
+      }
+    };
+    // A row moves when its tile maximum is more than 2^kLazyLog2 above the reference (the first tile's reference is
+    // -inf, so every row moves there).
+    auto exceeds = [&](float mx) __attribute__((always_inline)) { return (mx - m_ref) * scale_log2e > kLazyLog2; };
+
+    if constexpr (D == 256) {
+      // One wavefront per SIMD and every register in use: S cannot stay live across a first round of
+      // exponentials, so the row maximum is taken on every tile.
+      update_reference(exceeds);
+      stage_ahead();
+      exponentials();
+    } else {
+      // A tile first exponentiates against the reference it inherits and looks at the partial row sums: a P~
+      // above the limit makes the partial row sum of its lane exceed the limit.  Only then -- and on the first
+      // tile (reference -inf) and on tiles with masked entries (S holds -inf) -- does the wavefront take the row
+      // maximum, move the reference of the rows concerned and exponentiate again.  Which rows move is decided
+      // from the row's own values, never from another row's: on first and masked tiles by the maximum, otherwise
+      // by the row's two partial sums.  (Finite inputs and a finite reference: the sums are in [0, +inf].)
+      stage_ahead();
+      bool need_max = kMasked || jj == 0;   // wavefront-uniform
+      float sum_seen = 0.f;
+      if (!need_max) {
+        exponentials();
+        sum_seen = rowsum[0] + rowsum[1];
+        need_max = __builtin_amdgcn_ballot_w64(sum_seen > kLazyLimit) != 0;
+      }
+      if (need_max) {
+        update_reference([&](float mx) __attribute__((always_inline)) {
+          if (kMasked || jj == 0) return exceeds(mx);
+          const uint32_t u = __builtin_bit_cast(uint32_t, sum_seen);
+          const auto both = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+          return __builtin_bit_cast(float, (uint32_t)both[0]) > kLazyLimit ||
+                 __builtin_bit_cast(float, (uint32_t)both[1]) > kLazyLimit;
+        });
+        exponentials();
       }
     }
     l_run += rowsum[0] + rowsum[1];
@@ -433,133 +493,6 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     }
   };
 
-  // ---- stage pipeline (kPipe) ----
-  // One stage, kPar = s % 2 (also the half of the K/V tile its 32 keys are in).
-  //   kG2: O += P~_{s-1} V_{s-1}; v_half points at the 32 rows of V of stage s-1; P~ is pbuf[kPar ^ 1].
-  //   kG1: S_{s+1} = K_{s+1} Q^T into st[kPar ^ 1]; k_half points at the 32 rows of K of stage s+1.
-  //   kSm: softmax of st[kPar] into pbuf[kPar].  mask_on (uniform): the stage may hold masked keys; then
-  //        register v of S^T is masked when 8 (v/4) + v%4 > visible.
-  // The rescale of O that the softmax of stage s-1 decided is applied first: O then refers to the same
-  // reference point as P~_{s-1}.
-  auto stage = [&](auto g2_tag, auto g1_tag, auto sm_tag, auto par_tag, bool mask_on, int visible, const uint16_t* v_half,
-                   const uint16_t* k_half) __attribute__((always_inline)) {
-    constexpr bool kG2 = decltype(g2_tag)::value, kG1 = decltype(g1_tag)::value, kSm = decltype(sm_tag)::value;
-    constexpr int kPar = decltype(par_tag)::value;
-    constexpr int kN2 = 2 * kDBlocks, kN1 = kKSteps;   // MFMAs of the two products per stage (equal)
-    static_assert(kN1 == kN2, "the two products of a stage have the same number of MFMAs");
-    constexpr int kFull = kN1 + kN2;                   // MFMA slots of a complete stage
-    constexpr int kSlots = (kG2 ? kN2 : 0) + (kG1 ? kN1 : 0);
-    constexpr int kMaxSlots = kFull >= 16 ? 2 : 1;     // slots that hold the row maximum (8 pairs)
-    constexpr int kExpFirst = kMaxSlots + 2;           // then two slots for the reference point
-    constexpr int kExpSlots = kFull - kExpFirst;
-
-    if constexpr (kSm && (kCausal || kRagged)) {
-      if (mask_on) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (8 * (v / 4) + (v % 4) > visible) st[kPar][v] = -INFINITY;
-      }
-    }
-    if (kG2 && rescale_pend) {  // rare: the reference point moved in the previous softmax
-#pragma unroll
-      for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) ot[db][v] *= alpha_pend;
-    }
-
-    // MFMA step i of the stage: with both products, even steps belong to GEMM-II and odd steps to GEMM-I
-    auto frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
-      const bool second = (kG2 && kG1) ? (i & 1) == 0 : kG2;
-      const int idx = (kG2 && kG1) ? i / 2 : i;
-      if (second) {
-        const int t = idx / kDBlocks, db = idx % kDBlocks;
-        const uint16_t* p = v_half + v_addr[db] + t * 16 * D;
-        const u32x2 lo = lds_read_tr16(p);
-        const u32x2 hi = lds_read_tr16(p + 8 * D);
-        return u32x4{lo[0], lo[1], hi[0], hi[1]};
-      }
-      return *reinterpret_cast<const u32x4*>(k_half + k_addr[idx]);
-    };
-    u32x4 ring[kRing];
-#pragma unroll
-    for (int i = 0; i < kRing; ++i)
-      if (i < kSlots) ring[i] = frag(i);
-
-    float mx = 0.f, rs[2] = {0.f, 0.f}, p_even = 0.f;
-    bool move = false;
-    // Softmax work of slot m.  Every chunk hands its results to an empty asm statement, which keeps the
-    // optimiser from moving the arithmetic out of its slot (the results are only consumed a stage later).
-    auto softmax_chunk = [&](auto m_tag) __attribute__((always_inline)) {
-      constexpr int m = decltype(m_tag)::value;
-      if constexpr (m < kMaxSlots) {
-        constexpr int per = 8 / kMaxSlots;  // pairs per slot
-        static_for<per>([&](auto i_tag) {
-          constexpr int v = 2 * (m * per + decltype(i_tag)::value);
-          if constexpr (v == 0) mx = max2_raw(st[kPar][0], st[kPar][1]);
-          else mx = max3_raw(mx, st[kPar][v], st[kPar][v + 1]);
-        });
-        asm volatile("" : "+v"(mx));
-      } else if constexpr (m == kMaxSlots) {
-        mx = max_with_partner_half_raw(mx);
-        move = (mx - m_ref) * scale_log2e > kLazyLog2;  // lazy reference point, as in the plain form
-        asm volatile("" : "+v"(mx));
-      } else if constexpr (m == kMaxSlots + 1) {
-        const float m_new = move ? mx : m_ref;
-        const float mc_new = m_new * scale_log2e;
-        alpha_pend = move ? __builtin_amdgcn_exp2f(mc_ref - mc_new) : 1.0f;  // exactly 1 for a row that stays
-        m_ref = m_new;
-        mc_ref = mc_new;
-        l_run *= alpha_pend;
-        asm volatile("" : "+v"(alpha_pend), "+v"(mc_ref), "+v"(l_run));
-        rescale_pend = __builtin_amdgcn_ballot_w64(move) != 0;
-      } else if constexpr (m < kFull) {
-        constexpr int c = m - kExpFirst;
-        static_for<16>([&](auto e_tag) {
-          constexpr int v = decltype(e_tag)::value;
-          if constexpr (v * kExpSlots / 16 == c) {
-            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kPar][v], scale_log2e, -mc_ref));
-            rs[v & 1] += pv;  // fp32 rowsum of the unrounded P~
-            asm volatile("" : "+v"(rs[v & 1]));
-            if constexpr ((v & 1) == 0) {
-              p_even = pv;
-            } else {
-              uint32_t packed = E::pack2(p_even, pv);
-              asm volatile("" : "+v"(packed));
-              pbuf[kPar][v / 8][(v % 8) / 2] = packed;
-            }
-          }
-        });
-      }
-    };
-
-    static_for<kSlots>([&](auto i_tag) {
-      constexpr int i = decltype(i_tag)::value;
-      constexpr bool second = (kG2 && kG1) ? (i & 1) == 0 : kG2;
-      constexpr int idx = (kG2 && kG1) ? i / 2 : i;
-      if constexpr (second) {
-        constexpr int t = idx / kDBlocks, db = idx % kDBlocks;
-        ot[db] = E::mfma(ring[i % kRing], pbuf[kPar ^ 1][t], ot[db]);
-      } else if constexpr (idx == 0) {
-        f32x16 zero;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-        st[kPar ^ 1] = E::mfma(ring[i % kRing], qf[idx], zero);
-      } else {
-        st[kPar ^ 1] = E::mfma(ring[i % kRing], qf[idx], st[kPar ^ 1]);
-      }
-      if constexpr (i + kRing < kSlots) ring[i % kRing] = frag(i + kRing);
-      if constexpr (kSm) softmax_chunk(i_tag);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    if constexpr (kSm) {
-      // a stage without one of the products has fewer slots than chunks: the rest runs back to back
-      static_for<kFull - kSlots>([&](auto i_tag) {
-        softmax_chunk(std::integral_constant<int, decltype(i_tag)::value + kSlots>{});
-      });
-      l_run += rs[0] + rs[1];
-    }
-  };
-
   // LDS schedule.  K tile t lives in k_lds[t % kNBuf], V tile t in v_lds[t % kNBuf].  Iteration j reads
   // V tile j and K tile j+1 and ends with the one barrier per tile; after that barrier those two tiles are
   // dead and their buffers are refilled with K tile j+1+kNBuf and V tile j+kNBuf.  The loads needed by
@@ -579,7 +512,9 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
     else __builtin_amdgcn_s_waitcnt(kWaitAll);
     __syncthreads();
-    if (j + 1 + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, j + 1 + kNBuf, k_fill);
+    if constexpr (!kSplitRefill) {
+      if (j + 1 + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, j + 1 + kNBuf, k_fill);
+    }
     if (j + kNBuf < n_tiles) stage_in(false_type{}, v_rsrc, j + kNBuf, v_fill);
   };
 
@@ -610,70 +545,20 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
     __builtin_amdgcn_s_waitcnt(kWaitAll);
     __syncthreads();
-    if constexpr (kPipe) {
-      stage_in(false_type{}, v_rsrc, 1, v_lds1);  // n_tiles >= 2; waited for by the first barrier of the pipeline
-    } else {
+    {
       gemm1(k_lds0);
       __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
-      if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
+      if constexpr (!kSplitRefill) {
+        if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
+      }
       if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
     }
 
-    if constexpr (kPipe) {
-      // Stage pipeline.  Stage (t, h) is the h-th half of K/V tile t.  Step t = the stages (t-1, 1) and (t, 0): it
-      // reads K tile t (for S of stages (t,0) and (t,1)) and V tile t-1 (for the P~ of stages (t-1,0), (t-1,1)),
-      // and ends with the one barrier per tile, after which both are dead and are refilled with K tile t+2 and
-      // V tile t+1.  What step t+1 reads was issued one barrier earlier, so each barrier waits for everything.
-      using par0 = std::integral_constant<int, 0>;
-      using par1 = std::integral_constant<int, 1>;
-      constexpr int kHalf = 32 * D;  // elements of half a tile
-      alpha_pend = 1.f;
-      rescale_pend = false;
-      // visible key count of a stage, relative to its first key, minus this lane's 4 hh; only meaningful for the
-      // last two tiles (the others are never masked)
-      auto visible_of = [&](int t, int h) __attribute__((always_inline)) -> int {
-        int visible = kCausal ? wave * 32 + r - 4 * hh - (t - (n_tiles - 2)) * kBc - 32 * h
-                              : Nk - 1 - t * kBc - 32 * h - 4 * hh;
-        if constexpr (kCausal || kRagged) asm volatile("" : "+v"(visible));
-        return visible;
-      };
-      auto step_end = [&](int t) __attribute__((always_inline)) {  // t: the K tile this step has read
-        __builtin_amdgcn_s_waitcnt(kWaitAll);
-        __syncthreads();
-        if (t + 2 < n_tiles) stage_in(true_type{}, k_rsrc, t + 2, k_buf[t & 1]);
-        if (t >= 1 && t + 1 < n_tiles) stage_in(false_type{}, v_rsrc, t + 1, v_buf[(t + 1) & 1]);
-      };
-      // prologue (K tile 0 has been consumed up to its first half by gemm1's replacement below)
-      // Step 0: S of stage (0,0) alone, then stage (0,0): softmax, S of stage (0,1); no GEMM-II yet.
-      stage(false_type{}, true_type{}, false_type{}, par1{}, false, 0, v_lds0, k_lds0);            // S_(0,0) -> st[0]
-      stage(false_type{}, true_type{}, true_type{}, par0{}, n_tiles == 2, visible_of(0, 0), v_lds0, k_lds0 + kHalf);
-      step_end(0);
-      int t = 1;
-      for (; t + 1 < n_tiles; t += 2) {
-        const bool m1 = t + 1 >= n_tiles - 1;  // tile t-1 >= n_tiles - 2
-        const bool m2 = t + 2 >= n_tiles - 1;
-        // step t (odd): K tile t in k_lds1, V tile t-1 in v_lds0
-        stage(true_type{}, true_type{}, true_type{}, par1{}, m1, visible_of(t - 1, 1), v_lds0, k_lds1);
-        stage(true_type{}, true_type{}, true_type{}, par0{}, m2 && t >= n_tiles - 2, visible_of(t, 0), v_lds0 + kHalf, k_lds1 + kHalf);
-        step_end(t);
-        // step t+1 (even): K tile t+1 in k_lds0, V tile t in v_lds1
-        stage(true_type{}, true_type{}, true_type{}, par1{}, t >= n_tiles - 2, visible_of(t, 1), v_lds1, k_lds0);
-        stage(true_type{}, true_type{}, true_type{}, par0{}, t + 1 >= n_tiles - 2, visible_of(t + 1, 0), v_lds1 + kHalf, k_lds0 + kHalf);
-        step_end(t + 1);
-      }
-      // last step t = n_tiles - 1 (odd): K tile n-1 in k_lds1, V tile n-2 in v_lds0
-      stage(true_type{}, true_type{}, true_type{}, par1{}, true, visible_of(t - 1, 1), v_lds0, k_lds1);
-      stage(true_type{}, true_type{}, true_type{}, par0{}, true, visible_of(t, 0), v_lds0 + kHalf, k_lds1 + kHalf);
-      step_end(t);
-      // stage (n-1, 1): softmax and O += P~_(n-1,0) V; then the draining product O += P~_(n-1,1) V
-      stage(true_type{}, false_type{}, true_type{}, par1{}, true, visible_of(t, 1), v_lds1, k_lds0);
-      stage(true_type{}, false_type{}, false_type{}, par0{}, false, 0, v_lds1 + kHalf, k_lds0);
-    } else {
     int j = 0;
     for (; j + kNBuf < n_tiles; j += kNBuf) {  // every barrier of these iterations issues its full set of loads
       static_for<kNBuf>([&](auto t) {
         constexpr int i = decltype(t)::value;
-        iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf]);
+        iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(true_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
       });
     }
@@ -690,13 +575,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       // scalar registers for the whole loop
       if constexpr (mask_tail::value) asm volatile("" : "+v"(visible));
       if constexpr (i + 1 < kNBuf) {
-        iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
+        iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(false_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
       } else {
-        iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf]);
+        iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
       }
     });
-    }  // !kPipe
 
     // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
     const float l_tot = sum_with_partner_half(l_run);
@@ -720,357 +604,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   }  // pass
 }
 
-// -------------------------------------------------------------------------------------------------
-// Wide kernel: 64 query rows per wavefront, one workgroup (4 wavefronts, 256 rows) per CU.
-//
-// With 32 rows per wavefront every MFMA needs a fresh 1 KiB operand fragment from LDS, which at the
-// full MFMA rate is exactly the LDS bandwidth of a CU (128 B/clk): that design tops out on LDS.  Here a
-// fragment of K or V feeds two MFMAs (query halves A and B), which halves the LDS traffic per FLOP.  The
-// price is registers (O^T alone is 128 per lane at d=128), so only one wavefront fits a SIMD and the
-// overlap of softmax arithmetic with the matrix cores has to happen inside the instruction stream of
-// that one wavefront: the loop is software-pipelined over STAGES of 32 keys,
-//     stage s:   matrix cores:  S_{s+1} = K_{s+1} Q^T   and   O += P~_{s-1} V_{s-1}
-// and the softmax is cut into small chunks that are placed between the MFMAs in program order, so
-// they issue in the shadow of the 8-pass MFMAs.  (The paper's Section 6 overlaps copies with the two
-// GEMMs and leaves the softmax exposed; its register-pressure discussion in Section 7 is the same
-// trade-off that fixes the tile shape here.)
-constexpr int kWideBr = 64 * kWaves;  // query rows per workgroup of the wide kernel
-constexpr int kStageKeys = 32;        // keys per pipeline stage (half a K/V tile)
-
-template <int DT, int D>
-__global__ __launch_bounds__(kThreads, 1) void fa2_fwd_wide_kernel(const uint16_t* __restrict__ Q,
-                                                                   const uint16_t* __restrict__ K,
-                                                                   const uint16_t* __restrict__ V,
-                                                                   uint16_t* __restrict__ O, float* __restrict__ LSE,
-                                                                   int H, int N, float scale_log2e, int n_qtiles,
-                                                                   int total_tiles) {
-  using E = Elem<DT>;
-  using T = Tile<D>;
-  using std::false_type;
-  using std::true_type;
-  constexpr int kKSteps = D / 16;                // K fragments per stage (MFMA steps along d)
-  constexpr int kDBlocks = D / 32;               // 32-row blocks of O^T
-  constexpr int kVFrags = 2 * kDBlocks;          // V fragments per stage (2 key steps x d blocks)
-  constexpr int kFrags = kKSteps + kVFrags;      // operand fragments per stage, each feeds 2 MFMAs
-  constexpr int kSlots = 2 * kFrags;             // MFMAs per stage
-  constexpr int kRing = 4;                       // fragments in flight between LDS and the MFMAs
-  // softmax chunk schedule over the MFMA slots of a stage
-  constexpr int kMaxChunks = kSlots / 8;         // slots that hold the 16 v_max3 of the rowmax
-  constexpr int kMaxPerChunk = 8 / kMaxChunks;   // v_max3 per half and chunk
-  constexpr int kExpFirst = kMaxChunks + 2;      // first slot of the exponentials
-  constexpr int kExpChunks = kSlots - kExpFirst;
-
-  // Four buffers each for K and V tiles (128 KiB at d=128): global loads are issued three tiles ahead,
-  // far enough to cover an HBM miss.  Separate objects, so that the compiler can tell a load in flight
-  // into one buffer from the operand reads of another.
-  __shared__ __attribute__((aligned(1024))) uint16_t k_lds0[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t k_lds1[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t k_lds2[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t k_lds3[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t v_lds0[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t v_lds1[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t v_lds2[T::kElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t v_lds3[T::kElems];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int r = lane & 31;
-  const int hh = lane >> 5;
-
-  int tile;
-  {
-    const int wg = blockIdx.x;
-    const int per = total_tiles / kXcds, rem = total_tiles % kXcds;
-    const int xcd = wg % kXcds, idx = wg / kXcds;
-    tile = xcd * per + (xcd < rem ? xcd : rem) + idx;
-  }
-  const int bh = tile / n_qtiles;
-  const int qt = tile - bh * n_qtiles;
-  const int b = bh / H;
-  const int h = bh - b * H;
-
-  const size_t row_stride = (size_t)H * D;
-  const size_t head_base = ((size_t)b * N * H + (size_t)h) * D;
-  const size_t tile_stride = (size_t)kBc * row_stride;
-  const int q_row0 = qt * kWideBr + wave * 64 + r;  // half A; half B is 32 rows further
-
-  // Q fragments of both halves (B operands of S^T = K Q^T), resident for the whole loop.
-  u32x4 qf[2][kKSteps];
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const uint16_t* qp = Q + head_base + (size_t)(q_row0 + 32 * half) * row_stride + 8 * hh;
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) qf[half][ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
-  }
-
-  // Direct global->LDS staging, as in the narrow kernel.
-  const uint32_t head_bytes = (uint32_t)(((size_t)(N - 1) * row_stride + D) * 2);
-  const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(K + head_base), 0, (int)head_bytes, kBufferFlags);
-  const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(V + head_base), 0, (int)head_bytes, kBufferFlags);
-  const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
-  const uint32_t row_bytes = (uint32_t)(row_stride * 2);
-  // is_k is a compile-time tag: K and V tiles use different chunk swizzles.  The per-lane source offsets
-  // are recomputed at every call (a few integer operations per tile) instead of being kept in registers.
-  auto stage_in = [&](auto is_k, __amdgpu_buffer_rsrc_t rsrc, int j, uint16_t* lds_tile) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < T::kLoadsPerWave; ++i) {
-      const int chunk = 64 * (wave * T::kLoadsPerWave + i) + lane;
-      const int row = chunk / T::kChunksPerRow, pos = chunk % T::kChunksPerRow;
-      const int swz = decltype(is_k)::value ? T::swz_k(row) : T::swz_v(row);
-      const uint32_t src = (uint32_t)row * row_bytes + 16u * (uint32_t)(pos ^ swz);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(lds_tile + 512 * (wave * T::kLoadsPerWave + i)), 16,
-                                               (int)src, (int)((uint32_t)j * tile_bytes), 0, 0);
-    }
-  };
-
-  // Per-lane LDS element offsets of the operand reads inside a 32-key block.
-  int k_addr[kKSteps];
-#pragma unroll
-  for (int ks = 0; ks < kKSteps; ++ks) k_addr[ks] = r * D + 8 * ((2 * ks + hh) ^ T::swz_k(r));
-  int v_addr[kDBlocks];
-  {
-    const int l16 = lane & 15;
-    const int row0 = 4 * hh + (l16 >> 2);
-#pragma unroll
-    for (int db = 0; db < kDBlocks; ++db) {
-      const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((l16 & 3) >> 1);
-      v_addr[db] = row0 * D + 8 * (chunk ^ T::swz_v(row0)) + 4 * (l16 & 1);
-    }
-  }
-  // Fragment f of a stage: f < kKSteps is the K fragment of MFMA step f, otherwise the V fragment of
-  // key step t and d-block db with f - kKSteps = t * kDBlocks + db.
-  auto frag = [&](const uint16_t* k_blk, const uint16_t* v_blk, int f) __attribute__((always_inline)) -> u32x4 {
-    if (f < kKSteps) return *reinterpret_cast<const u32x4*>(k_blk + k_addr[f]);
-    const int g = f - kKSteps, t = g / kDBlocks, db = g % kDBlocks;
-    const uint16_t* p = v_blk + v_addr[db] + t * 16 * D;
-    const u32x2 lo = lds_read_tr16(p);
-    const u32x2 hi = lds_read_tr16(p + 8 * D);
-    return u32x4{lo[0], lo[1], hi[0], hi[1]};
-  };
-
-  // State of Algorithm 2 for the two query halves.
-  f32x16 ot[2][kDBlocks];
-#pragma unroll
-  for (int half = 0; half < 2; ++half)
-#pragma unroll
-    for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) ot[half][db][v] = 0.f;
-  f32x16 st[2][2];      // [pipeline slot][half]: S^T of a 32-key stage
-  u32x4 pf[2][2][2];    // [pipeline slot][half][key step]: P~ rounded to 16 bit, B operands of GEMM-II
-  float m_ref[2] = {-INFINITY, -INFINITY};
-  float mc_ref[2] = {-INFINITY, -INFINITY};
-  float l_run[2] = {0.f, 0.f};
-  float alpha_pend[2] = {1.f, 1.f};  // rescale of O decided by the previous stage's softmax, not yet applied
-  bool rescale_pend = false;
-
-  // One pipeline stage.  kG1: compute S of the next stage from k_blk into st[kSlot ^ 1];
-  // kSm: softmax of st[kSlot] into pf[kSlot]; kG2: O += P~ V with pf[kSlot ^ 1] and v_blk.
-  auto stage = [&](auto g1_tag, auto sm_tag, auto g2_tag, auto slot_tag, const uint16_t* k_blk,
-                   const uint16_t* v_blk) __attribute__((always_inline)) {
-    constexpr bool kG1 = decltype(g1_tag)::value, kSm = decltype(sm_tag)::value, kG2 = decltype(g2_tag)::value;
-    constexpr int kSlot = decltype(slot_tag)::value;
-    constexpr int kFirst = kG1 ? 0 : kKSteps;          // first and one-past-last fragment of this stage
-    constexpr int kLast = kG2 ? kFrags : kKSteps;
-
-    if (kG2 && rescale_pend) {  // rare: the reference point moved in the previous stage
-#pragma unroll
-      for (int half = 0; half < 2; ++half)
-#pragma unroll
-        for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) ot[half][db][v] *= alpha_pend[half];
-    }
-
-    u32x4 ring[kRing];
-#pragma unroll
-    for (int i = 0; i < kRing; ++i)
-      if (kFirst + i < kLast) ring[i] = frag(k_blk, v_blk, kFirst + i);
-
-    float mx[2], rs[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, pe[2] = {0.f, 0.f};
-    // softmax work of MFMA slot m.  Every chunk ends by handing its results to an empty asm statement:
-    // that keeps the optimiser from sinking the arithmetic out of its slot (its results are only
-    // consumed in the next stage).
-    auto softmax_chunk = [&](auto m_tag) __attribute__((always_inline)) {
-      constexpr int m = decltype(m_tag)::value;
-      if constexpr (m < kMaxChunks) {
-        static_for<2>([&](auto half_tag) {
-          constexpr int half = decltype(half_tag)::value;
-          static_for<kMaxPerChunk>([&](auto i_tag) {
-            constexpr int v = 2 * (m * kMaxPerChunk + decltype(i_tag)::value);
-            if constexpr (v == 0) mx[half] = max2_raw(st[kSlot][half][0], st[kSlot][half][1]);
-            else mx[half] = max3_raw(mx[half], st[kSlot][half][v], st[kSlot][half][v + 1]);
-          });
-          asm volatile("" : "+v"(mx[half]));
-        });
-      } else if constexpr (m == kMaxChunks) {
-        static_for<2>([&](auto half_tag) {
-          constexpr int half = decltype(half_tag)::value;
-          mx[half] = max_with_partner_half_raw(mx[half]);
-          asm volatile("" : "+v"(mx[half]));
-        });
-      } else if constexpr (m == kMaxChunks + 1) {
-        // lazy reference point, see the narrow kernel: move only when exceeded by 2^kLazyLog2
-        bool move[2];
-        static_for<2>([&](auto half_tag) {
-          constexpr int half = decltype(half_tag)::value;
-          move[half] = (mx[half] - m_ref[half]) * scale_log2e > kLazyLog2;
-          const float m_new = move[half] ? mx[half] : m_ref[half];
-          const float mc_new = m_new * scale_log2e;
-          alpha_pend[half] = move[half] ? __builtin_amdgcn_exp2f(mc_ref[half] - mc_new) : 1.0f;  // exactly 1 for a row that stays
-          m_ref[half] = m_new;
-          mc_ref[half] = mc_new;
-          l_run[half] *= alpha_pend[half];
-          asm volatile("" : "+v"(alpha_pend[half]), "+v"(mc_ref[half]), "+v"(l_run[half]));
-        });
-        rescale_pend = __builtin_amdgcn_ballot_w64(move[0] || move[1]) != 0;
-      } else if constexpr (m < kSlots) {
-        constexpr int c = m - kExpFirst;
-        static_for<32>([&](auto e_tag) {
-          constexpr int e = decltype(e_tag)::value;
-          if constexpr (e * kExpChunks / 32 == c) {
-            constexpr int half = (e >> 1) & 1, v = 2 * (e >> 2) + (e & 1);
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kSlot][half][v], scale_log2e, -mc_ref[half]));
-            rs[half][e & 1] += p;  // fp32 rowsum of the unrounded P~
-            asm volatile("" : "+v"(rs[half][e & 1]));
-            if constexpr ((e & 1) == 0) {
-              pe[half] = p;
-            } else {
-              uint32_t packed = E::pack2(pe[half], p);
-              asm volatile("" : "+v"(packed));
-              pf[kSlot][half][v / 8][(v % 8) / 2] = packed;
-            }
-          }
-        });
-      }
-    };
-
-    static_for<2 * (kLast - kFirst)>([&](auto i_tag) {
-      constexpr int i = decltype(i_tag)::value;  // slot of this stage
-      constexpr int f = kFirst + i / 2, half = i % 2;
-      const u32x4 a = ring[(f - kFirst) % kRing];
-      if constexpr (f < kKSteps) {
-        if constexpr (f == 0) {
-          f32x16 zero;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-          st[kSlot ^ 1][half] = E::mfma(a, qf[half][f], zero);
-        } else {
-          st[kSlot ^ 1][half] = E::mfma(a, qf[half][f], st[kSlot ^ 1][half]);
-        }
-      } else {
-        constexpr int g = f - kKSteps, t = g / kDBlocks, db = g % kDBlocks;
-        ot[half][db] = E::mfma(a, pf[kSlot ^ 1][half][t], ot[half][db]);
-      }
-      if constexpr (half == 1 && f + kRing < kLast) ring[(f - kFirst) % kRing] = frag(k_blk, v_blk, f + kRing);
-      if constexpr (kSm) softmax_chunk(i_tag);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    if constexpr (kSm) {
-      // stages without GEMM-I or GEMM-II have fewer slots than chunks: run the rest back to back
-      static_for<kSlots - 2 * (kLast - kFirst)>([&](auto i_tag) {
-        softmax_chunk(std::integral_constant<int, decltype(i_tag)::value + 2 * (kLast - kFirst)>{});
-      });
-#pragma unroll
-      for (int half = 0; half < 2; ++half) l_run[half] += rs[half][0] + rs[half][1];
-    }
-  };
-
-  using slot0 = std::integral_constant<int, 0>;
-  using slot1 = std::integral_constant<int, 1>;
-
-  // Pipeline over stages s = 0 .. n_stages (inclusive): stage s runs softmax(s), GEMM-I(s+1), GEMM-II(s-1).
-  // K tile t (blocks 2t, 2t+1) sits in k_lds[t % 4], V tile t in v_lds[t % 4].  Tile step j is the pair
-  // of stages 2j+1, 2j+2: it reads K tile j+1 and V tile j and ends with the one barrier per tile.  After
-  // that barrier K tile j+1 and V tile j are dead and their buffers are refilled with K tile j+5 and
-  // V tile j+4.  The loads needed by step j+1 (K tile j+2, V tile j+1) were issued three barriers
-  // earlier; each barrier issues 2*kLoadsPerWave loads per wavefront, so waiting until at most
-  // 2*(2*kLoadsPerWave) are outstanding is enough while every barrier issues its full set.
-  constexpr int kLoadsPerBarrier = 2 * T::kLoadsPerWave;
-  constexpr int kRelaxedVmcnt = 2 * kLoadsPerBarrier;
-  static_assert(kRelaxedVmcnt < 64, "vmcnt is a 6-bit counter");
-  // s_waitcnt immediate with expcnt and lgkmcnt left at their maximum (no wait)
-  constexpr int kWaitRelaxed = (kRelaxedVmcnt & 15) | ((kRelaxedVmcnt >> 4) << 14) | 0x0F70;
-  constexpr int kWaitAll = 0x0F70;  // vmcnt(0)
-
-  const int n_tiles = N / kBc;  // a multiple of 4 because N is a multiple of 256
-  stage_in(true_type{}, k_rsrc, 0, k_lds0);
-  stage_in(false_type{}, v_rsrc, 0, v_lds0);
-  stage_in(true_type{}, k_rsrc, 1, k_lds1);
-  stage_in(false_type{}, v_rsrc, 1, v_lds1);
-  stage_in(true_type{}, k_rsrc, 2, k_lds2);
-  stage_in(false_type{}, v_rsrc, 2, v_lds2);
-  stage_in(true_type{}, k_rsrc, 3, k_lds3);
-  // The Q fragments are only ever read by MFMAs, which can take an operand straight from the accumulation
-  // registers: park them there and leave the architectural registers to the softmax.  (This also makes the
-  // loads complete here, so that no wait for them lands inside the loop.)
-#pragma unroll
-  for (int half = 0; half < 2; ++half)
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+a"(qf[half][ks]));
-  __builtin_amdgcn_s_waitcnt(kWaitAll);
-  __syncthreads();
-
-  // prologue: GEMM-I(0) alone, then stage 0 (no GEMM-II yet)
-  stage(true_type{}, false_type{}, false_type{}, slot1{}, k_lds0, v_lds0);                 // writes st[0]
-  stage(true_type{}, true_type{}, false_type{}, slot0{}, k_lds0 + kStageKeys * D, v_lds0);  // softmax(0), S_1 -> st[1]
-  __syncthreads();  // everyone is done with K tile 0
-  if (4 < n_tiles) stage_in(true_type{}, k_rsrc, 4, k_lds0);
-  stage_in(false_type{}, v_rsrc, 3, v_lds3);
-
-  auto tile_step = [&](auto relaxed_tag, int j, const uint16_t* k_next, const uint16_t* v_cur, uint16_t* k_fill,
-                       uint16_t* v_fill) __attribute__((always_inline)) {
-    // stage 2j+1: softmax(2j+1), S_{2j+2} from K tile j+1 first half, O += P~_{2j} V (V tile j first half)
-    stage(true_type{}, true_type{}, true_type{}, slot1{}, k_next, v_cur);
-    // stage 2j+2: softmax(2j+2), S_{2j+3} from K tile j+1 second half, O += P~_{2j+1} V (V tile j second half)
-    stage(true_type{}, true_type{}, true_type{}, slot0{}, k_next + kStageKeys * D, v_cur + kStageKeys * D);
-    // this wavefront's parts of K tile j+2 and V tile j+1 have landed ...
-    if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
-    else __builtin_amdgcn_s_waitcnt(kWaitAll);
-    __syncthreads();  // ... and everybody's; and nobody reads K tile j+1 / V tile j any more
-    if (j + 5 < n_tiles) stage_in(true_type{}, k_rsrc, j + 5, k_fill);
-    if (j + 4 < n_tiles) stage_in(false_type{}, v_rsrc, j + 4, v_fill);
-  };
-  int j = 0;
-  for (; j + 8 <= n_tiles; j += 4) {  // every barrier of these steps issues its full set of loads
-    tile_step(true_type{}, j, k_lds1, v_lds0, k_lds1, v_lds0);
-    tile_step(true_type{}, j + 1, k_lds2, v_lds1, k_lds2, v_lds1);
-    tile_step(true_type{}, j + 2, k_lds3, v_lds2, k_lds3, v_lds2);
-    tile_step(true_type{}, j + 3, k_lds0, v_lds3, k_lds0, v_lds3);
-  }
-  // tail: j = n_tiles - 4; three more full steps, then the two draining stages
-  tile_step(false_type{}, j, k_lds1, v_lds0, k_lds1, v_lds0);
-  tile_step(false_type{}, j + 1, k_lds2, v_lds1, k_lds2, v_lds1);
-  tile_step(false_type{}, j + 2, k_lds3, v_lds2, k_lds3, v_lds2);
-  // last softmax stage (S of the last 32 keys was produced by the stage before): no GEMM-I
-  stage(false_type{}, true_type{}, true_type{}, slot1{}, k_lds0, v_lds3);
-  // draining stage: only O += P~_{last} V
-  stage(false_type{}, false_type{}, true_type{}, slot0{}, k_lds0, v_lds3 + kStageKeys * D);
-
-  // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum).
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const float l_tot = sum_with_partner_half(l_run[half]);
-    const float inv_l = 1.0f / l_tot;
-    const int q_row = q_row0 + 32 * half;
-    uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
-#pragma unroll
-    for (int db = 0; db < kDBlocks; ++db) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w = {E::pack2(ot[half][db][4 * g + 0] * inv_l, ot[half][db][4 * g + 1] * inv_l),
-                   E::pack2(ot[half][db][4 * g + 2] * inv_l, ot[half][db][4 * g + 3] * inv_l)};
-        *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
-      }
-    }
-    if (LSE != nullptr && hh == 0) {
-      LSE[((size_t)b * H + h) * N + q_row] = mc_ref[half] * 0.69314718055994530942f + __builtin_logf(l_tot);
-    }
-  }
-}
+constexpr int kRows256 = 256;  // query rows per workgroup of the 8-wavefront shape
 
 // Enqueues `kernel` and reports this launch's own status (not whatever error an earlier, unrelated HIP call left).
 template <class... Params, class... Args>
@@ -1084,10 +618,10 @@ int enqueue(void (*kernel)(Params...), int grid, int block, hipStream_t stream, 
 }
 
 // One instantiation of the 32-row kernel.
-template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged, bool kPipe = false>
+template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
 int launch_rows32(const void* Q, const void* K, const void* V, void* O, float* LSE, int H, int Nq, int Nk,
                   float scale_log2e, int n_qtiles, int total, hipStream_t stream) {
-  return enqueue(fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged, kPipe>, total, kWv * 64, stream,
+  return enqueue(fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged>, total, kWv * 64, stream,
                  static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V),
                  static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles, total);
 }
@@ -1096,10 +630,10 @@ template <int DT, int D>
 int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, float scale,
            int variant, int mask, hipStream_t stream) {
   const float scale_log2e = scale * 1.44269504088896340736f;
-  const bool rows256 = variant == FA2_VARIANT_WIDE || variant == FA2_VARIANT_NARROW8;
+  const bool rows256 = variant == FA2_VARIANT_NARROW8;
   const bool causal = mask == FA2_MASK_CAUSAL;
   const bool ragged = Nq % kBr != 0 || Nk % kBr != 0;  // 128-row shape only (checked by the caller)
-  const int rows = rows256 ? kWideBr : kBr;
+  const int rows = rows256 ? kRows256 : kBr;
   const int n_qtiles = (Nq + rows - 1) / rows;
   // causal: one workgroup per pair of Q tiles (n_qtiles-1-p, p)
   const long long total_ll = (long long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);
@@ -1107,18 +641,7 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   const int total = (int)total_ll;
   if (rows256) {  // exact tiles, no mask, d <= 128 (checked by the caller)
     if constexpr (D <= 128) {
-      if (variant == FA2_VARIANT_WIDE) {
-        return enqueue(fa2_fwd_wide_kernel<DT, D>, total, kThreads, stream, static_cast<const uint16_t*>(Q),
-                       static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), LSE,
-                       H, Nq, scale_log2e, n_qtiles, total);
-      }
       return launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
-    } else {
-      return FA2_ERR_UNSUPPORTED;
-    }
-  } else if (variant == FA2_VARIANT_PIPE) {  // whole tiles, no mask, d <= 128 (checked by the caller)
-    if constexpr (D <= 128) {
-      return launch_rows32<DT, D, 4, 2, false, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
     } else {
       return FA2_ERR_UNSUPPORTED;
     }
@@ -1140,8 +663,7 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if (!(scale > 0.0f) || !(scale <= 3.0e38f)) return FA2_ERR_INVALID_ARG;  // rejects NaN, inf, <= 0
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(LSE, 4))
     return FA2_ERR_INVALID_ARG;
-  if (variant != FA2_VARIANT_AUTO && variant != FA2_VARIANT_NARROW && variant != FA2_VARIANT_WIDE &&
-      variant != FA2_VARIANT_NARROW8 && variant != FA2_VARIANT_PIPE)
+  if (variant != FA2_VARIANT_AUTO && variant != FA2_VARIANT_NARROW && variant != FA2_VARIANT_NARROW8)
     return FA2_ERR_INVALID_ARG;
   if (mask != FA2_MASK_NONE && mask != FA2_MASK_CAUSAL) return FA2_ERR_INVALID_ARG;
   if (dtype != FA2_FP16 && dtype != FA2_BF16) return FA2_ERR_UNSUPPORTED;
@@ -1160,9 +682,8 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
     variant = FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {
-    // the other shapes and schedules exist for sweeps: whole tiles, square, unmasked, d <= 128
-    const int rows = variant == FA2_VARIANT_PIPE ? kBr : kWideBr;
-    if (Nq != Nk || Nq % rows != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
+    // the 256-row shape exists for tile-shape sweeps: whole tiles, square, unmasked, d <= 128
+    if (Nq != Nk || Nq % kRows256 != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
@@ -1201,7 +722,7 @@ extern "C" const char* fa2_strerror(int code) {
   switch (code) {
     case FA2_OK: return "success";
     case FA2_ERR_INVALID_ARG: return "invalid argument (NULL or misaligned pointer, non-positive size, scale not finite and > 0, or unknown variant or mask)";
-    case FA2_ERR_UNSUPPORTED: return "unsupported problem (d must be 64, 128 or 256; dtype fp16 or bf16; the causal mask needs Nq == Nk; the 256-row tile shapes need d <= 128 and N a multiple of 256; sizes must fit 32-bit offsets)";
+    case FA2_ERR_UNSUPPORTED: return "unsupported problem (d must be 64, 128 or 256; dtype fp16 or bf16; the causal mask needs Nq == Nk; the 256-row tile shape needs d <= 128 and N a multiple of 256; sizes must fit 32-bit offsets)";
     case FA2_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     default: return "unknown fa2 error code";
   }

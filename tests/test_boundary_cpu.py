@@ -87,11 +87,12 @@ _OKARGS = dict(q=P, k=P, v=P, o=P, lse=P, B=1, H=2, N=256, d=64, scale=0.125, dt
 @pytest.mark.parametrize("variant,args,code", [
     (99, {}, fa2.FA2_ERR_INVALID_ARG),                                 # unknown tile shape
     (-1, {}, fa2.FA2_ERR_INVALID_ARG),
-    (fa2.FA2_VARIANT_WIDE, dict(N=384), fa2.FA2_ERR_UNSUPPORTED),      # 256-row shapes need N % 256 == 0
+    (fa2.FA2_VARIANT_NARROW8, dict(N=384), fa2.FA2_ERR_UNSUPPORTED),   # the 256-row shape needs N % 256 == 0
+    (2, {}, fa2.FA2_ERR_INVALID_ARG),                                  # values 2 and 4 are not tile shapes
+    (4, {}, fa2.FA2_ERR_INVALID_ARG),
     (fa2.FA2_VARIANT_NARROW8, dict(N=128), fa2.FA2_ERR_UNSUPPORTED),
     (fa2.FA2_VARIANT_NARROW, dict(d=32), fa2.FA2_ERR_UNSUPPORTED),
-    (fa2.FA2_VARIANT_WIDE, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),      # d=256 runs on the 128-row shape only
-    (fa2.FA2_VARIANT_NARROW8, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),
+    (fa2.FA2_VARIANT_NARROW8, dict(d=256), fa2.FA2_ERR_UNSUPPORTED),   # d=256 runs on the 128-row shape only
     (fa2.FA2_VARIANT_NARROW, dict(q=None), fa2.FA2_ERR_INVALID_ARG),
 ])
 def test_variant_entry_rejects_bad_arguments_without_a_launch(variant, args, code):
