@@ -363,6 +363,10 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     // Row maximum of this tile (both halves of the wavefront), the move of the reference point for the rows that
     // `moves(mx)` selects, and the rescale of l and O.
     auto update_reference = [&](auto moves) __attribute__((always_inline)) {
+      // The maxima below are inline assembly, for which the compiler inserts no wait states: S^T may have been
+      // written by an MFMA (8 passes) shortly before, so the distance an MFMA result needs before a vector
+      // instruction may read it is put here by hand (this path runs on first, masked and rare tiles only).
+      asm volatile("s_nop 15\n\ts_nop 3");
       float mx = max2_raw(st[0][0], st[0][1]);
 #pragma unroll
       for (int kb = 0; kb < kKBlocks; ++kb)
