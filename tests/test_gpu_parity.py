@@ -318,3 +318,52 @@ def test_concurrent_launches_from_threads_on_their_own_streams():
     for i, (_, _, _, _, o_seq, lse_seq) in enumerate(jobs):
         for o, lse in results[i]:
             assert torch.equal(o, o_seq) and torch.equal(lse, lse_seq), f"job {i} differs under concurrency"
+
+
+# ------------------------------------------------------------------ the reference point of the exponentials
+def test_rows_do_not_depend_on_their_neighbours_bitwise():
+    # Whether the reference point of a row moves is decided from that row's own values: permuting the query rows
+    # (so that every row gets other neighbours in its wavefront, some with outlier logits that force their own
+    # reference to move) must permute the output rows bit for bit.
+    B, H, N, d = 1, 2, 1024, 128
+    print("row independence under a permutation of the queries", flush=True)
+    qb, kb, vb = workloads.make_qkv(B, N, H, d, "fp16", 8181, k_outlier_frac=0.03, k_outlier_gain=8.0)
+    # a third of the queries are scaled up as well: their logits overflow the inherited reference in many tiles
+    q = oracle.widen(qb, "fp16")
+    q[:, ::3] *= 4.0
+    qb = workloads.round_to_bits(q.astype(np.float32), "fp16")
+    perm = np.random.Generator(np.random.PCG64(9)).permutation(N)
+    o0, l0 = run_gpu(qb, kb, vb, "fp16", 0.0884, bits=True)
+    o1, l1 = run_gpu(np.ascontiguousarray(qb[:, perm]), kb, vb, "fp16", 0.0884, bits=True)
+    assert np.array_equal(o1, o0[:, perm])
+    assert np.array_equal(l1.view(np.uint32), l0[:, :, perm].view(np.uint32))
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("d", [64, 128])
+def test_reference_point_moves_tile_after_tile(d, dtype):
+    # Keys ordered so that the logits of every query grow from tile to tile by more than the 2^8 the inherited
+    # reference tolerates: every K/V tile overflows it, the row maximum is taken and O, l are rescaled each time
+    # (what Algorithm 2 does on every tile).  The opposite order never moves the reference after the first tile.
+    B, H, N = 1, 2, 1024
+    print(f"growing logits d={d} {dtype}", flush=True)
+    r = np.random.Generator(np.random.PCG64(77 + d))
+    u = r.standard_normal((B, 1, H, d)).astype(np.float32)
+    u /= np.linalg.norm(u, axis=-1, keepdims=True)
+    q = (u * 6.0 + 0.1 * r.standard_normal((B, N, H, d))).astype(np.float32)         # every query near 6 u
+    ramp = np.linspace(-1.0, 1.0, N, dtype=np.float32)[None, :, None, None]
+    # scaled logit of key j: 45 ramp_j, i.e. 5.6 nats (8.1 in log2 units) more per tile of 64 keys
+    k = (u * 45.0 * ramp * np.sqrt(d) / 6.0 + 0.05 * r.standard_normal((B, N, H, d))).astype(np.float32)
+    v = r.standard_normal((B, N, H, d)).astype(np.float32)
+    scale = float(1.0 / np.sqrt(d))
+    for order in (slice(None), slice(None, None, -1)):
+        qb, kb, vb = (workloads.round_to_bits(np.ascontiguousarray(x), dtype) for x in (q, k[:, order], v[:, order]))
+        o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
+        o, lse = run_gpu(qb, kb, vb, dtype, scale)
+        if dtype == "bf16":
+            # nearly one-hot rows reproduce single V rows: outputs of magnitude up to 4, beyond the reach of 1e-2 for
+            # a bf16 output (half an ulp in [2, 4) is 7.8e-3 before any arithmetic); bound relative to |O| instead
+            assert np.all(np.abs(o - o_ref) <= np.maximum(TOL_O_MAX, np.abs(o_ref) * 2.0 ** -7))
+            assert np.max(np.abs(lse - lse_ref)) <= TOL_LSE_MAX
+        else:
+            check(o, lse, o_ref, lse_ref, f"growing logits d{d} {dtype} order {order.step}")
