@@ -732,4 +732,4 @@ extern "C" const char* fa2_strerror(int code) {
   }
 }
 
-extern "C" int fa2_version(void) { return 300; /* 0.3.0 */ }
+extern "C" int fa2_version(void) { return 400; /* 0.4.0 */ }
