@@ -42,6 +42,7 @@ constexpr int kWaves = 4;            // wavefronts per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kBr = 32 * kWaves;     // query rows per workgroup (32 per wavefront)
 constexpr int kBc = 64;              // keys per K/V tile
+constexpr int kSpinLimit = 1 << 18;  // polls of the arrival count before a wavefront gives up (tens of milliseconds)
 constexpr int kXcds = 8;             // accelerator complex dies; workgroup i is dispatched to XCD i % 8
 constexpr float kLazyLog2 = 8.0f;    // the rowmax reference moves only when exceeded by 2^8
 
@@ -174,6 +175,11 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   constexpr int kRing = 4;                     // operand fragments in flight between LDS and the MFMAs
   constexpr int kLoadsPerWave = T::kElems * 2 / 1024 / kWv;  // 1 KiB wavefront loads per tile and wavefront
   constexpr bool kSplitRefill = kNBuf == 2 && D == 256;    // K and V refills issued as two separate bursts
+  // The 8-wavefront shape has no barrier in its loop: its wavefronts count their arrivals at the end of every
+  // iteration in LDS and go on as soon as all have finished the iteration BEFORE.  One barrier per tile would
+  // start the two wavefronts of every SIMD in the same phase tile after tile, softmax against softmax and MFMAs
+  // against MFMAs; with a tile of slack they drift apart and fill each other's gaps.
+  constexpr bool kFlagSync = kWv == 8;
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
   // buffer cannot alias the operand reads from another.  (With kNBuf == 2 the last two pairs are unused.)
@@ -185,6 +191,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds1[T::kElems];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds2[kNBuf == 4 ? T::kElems : 8];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds3[kNBuf == 4 ? T::kElems : 8];
+  __shared__ uint32_t arrivals[4];  // kFlagSync: wavefronts that finished iteration j, counted in entry j % 4
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -331,6 +338,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // mask_tag: the tile straddles the causal diagonal; `visible` is then the largest value of
   // 32 kb + 8 (v/4) + v%4 (the key's position in the tile minus this half's 4 hh) that register v of key
   // block kb may have for its key to be at or before this lane's query.
+  bool hurry = false;  // kFlagSync: this wavefront did not have to wait at its last boundary, so it is among the slowest
   auto iteration = [&](auto next_tag, auto mask_tag, int visible, const uint16_t* v_cur, const uint16_t* k_next,
                        int jj, uint16_t* k_refill) __attribute__((always_inline)) {
     if constexpr (decltype(mask_tag)::value) {
@@ -349,7 +357,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     // The reference point m of the exponentials only has to keep them in range, it need not be the running
     // maximum of Algorithm 2: the result is unchanged because the reference cancels in O / l.  It is moved (and
     // O, l rescaled by exp(m_old - m_new)) only when a tile would otherwise produce a P~ above 2^kLazyLog2.
-    __builtin_amdgcn_s_setprio(0);
+    if (kFlagSync && hurry) __builtin_amdgcn_s_setprio(2);
+    else __builtin_amdgcn_s_setprio(0);
     constexpr bool kMasked = decltype(mask_tag)::value;
     constexpr float kLazyLimit = 256.0f;  // 2^kLazyLog2
     // d = 256 takes the maximum on every tile and skips the rescale when no row of the wavefront moves; the lazy
@@ -470,7 +479,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     // 16t + 8(i/4) + 4hh + i%4, the key of accumulator register 8t+i of GEMM-I.  GEMM-I of the next tile
     // follows in the same stream of MFMA steps, so its first K fragments are fetched under the last MFMAs of
     // GEMM-II and no LDS latency is exposed between the two products.
-    __builtin_amdgcn_s_setprio(1);
+    if (kFlagSync && hurry) __builtin_amdgcn_s_setprio(3);
+    else __builtin_amdgcn_s_setprio(1);
     constexpr bool kNext = decltype(next_tag)::value;
     constexpr int kStepsAll = kSteps2 + (kNext ? kSteps1 : 0);
     auto any_frag = [&](int step) __attribute__((always_inline)) -> u32x4 {
@@ -513,6 +523,36 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
 
   // end of iteration j: publish what iteration j+1 reads, then refill the two dead buffers
   auto boundary = [&](auto relaxed_tag, int j, uint16_t* k_fill, uint16_t* v_fill) __attribute__((always_inline)) {
+    if constexpr (kFlagSync) {
+      // Arrival j of a wavefront says: my reads of V tile j and K tile j+1 are over, and my share of the loads
+      // issued at the previous boundary (K tile j+3, V tile j+2) has landed.  A wavefront leaves boundary j when
+      // every wavefront has made arrival j-1: then K tile j+2 and V tile j+1, which iteration j+1 reads, are
+      // complete, and V tile j-1 and K tile j are dead, so their buffers (k_fill, v_fill) take K tile j+kNBuf and
+      // V tile j-1+kNBuf.  A wavefront makes arrival j before it waits for the others' arrival j-1, so it can be two
+      // arrivals ahead of the slowest: arrivals are counted per iteration, iteration j in entry j % 4 (entries are
+      // reused four iterations later, far beyond that lead), and arrival j-1 is complete when its entry has
+      // reached kWv * ((j-1)/4 + 1).  The wait is bounded: a wavefront that gives up poisons its rowsum, so the
+      // error shows in O and LSE instead of hanging the GPU.
+      // a first look at the others' count, under way while this wavefront waits for its own loads
+      uint32_t seen = __hip_atomic_load(&arrivals[(j + 3) & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      __builtin_amdgcn_s_waitcnt(kWaitAll);
+      if (lane == 0) __hip_atomic_fetch_add(&arrivals[j & 3], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const uint32_t target = j > 0 ? (uint32_t)(kWv * ((j - 1) / 4 + 1)) : 0u;
+      int spins = 0;
+      while (seen < target) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > kSpinLimit) {
+          l_run = __builtin_nanf("");
+          break;
+        }
+        seen = __hip_atomic_load(&arrivals[(j + 3) & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the tiles are read only after the count was seen
+      hurry = spins == 0;
+      if (j + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, j + kNBuf, k_fill);
+      if (j - 1 + kNBuf < n_tiles) stage_in(false_type{}, v_rsrc, j - 1 + kNBuf, v_fill);
+      return;
+    }
     if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
     else __builtin_amdgcn_s_waitcnt(kWaitAll);
     __syncthreads();
@@ -521,6 +561,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     }
     if (j + kNBuf < n_tiles) stage_in(false_type{}, v_rsrc, j + kNBuf, v_fill);
   };
+  // buffers refilled at the boundary after iteration j+i of a group of kNBuf iterations (see `boundary`)
+  constexpr int kKFillShift = kFlagSync ? 0 : 1, kVFillShift = kFlagSync ? kNBuf - 1 : 0;
 
   for (int pass = 0; pass < n_pass; ++pass) {
     if (pass > 0) __syncthreads();  // the first Q tile's last K/V reads are over before the buffers are refilled
@@ -548,14 +590,17 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
 #pragma unroll
     for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
     __builtin_amdgcn_s_waitcnt(kWaitAll);
+    if (kFlagSync && tid < 4) arrivals[tid] = 0;
     __syncthreads();
     {
       gemm1(k_lds0);
       __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
-      if constexpr (!kSplitRefill) {
-        if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
+      if constexpr (!kFlagSync) {   // (with kFlagSync the first boundary issues these two)
+        if constexpr (!kSplitRefill) {
+          if (kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, kNBuf, k_lds0);
+        }
+        if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
       }
-      if (kNBuf - 1 < n_tiles) stage_in(false_type{}, v_rsrc, kNBuf - 1, v_buf[kNBuf - 1]);
     }
 
     int j = 0;
@@ -563,7 +608,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       static_for<kNBuf>([&](auto t) {
         constexpr int i = decltype(t)::value;
         iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
-        boundary(true_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
+        boundary(true_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
       });
     }
     // last kNBuf tiles: wait for everything, and the very last tile has no successor.  Under the causal mask
@@ -580,7 +625,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       if constexpr (mask_tail::value) asm volatile("" : "+v"(visible));
       if constexpr (i + 1 < kNBuf) {
         iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
-        boundary(false_type{}, j + i, k_buf[(i + 1) % kNBuf], v_buf[i]);
+        boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
       } else {
         iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
       }
