@@ -76,8 +76,10 @@ enum {
   FA2_VARIANT_NARROW = 1, /* 128 query rows per workgroup (4 wavefronts x 32 rows), 2 workgroups per CU,
                              K/V tiles of 64 keys double-buffered in LDS                                */
   FA2_VARIANT_NARROW8 = 3 /* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
-                             K/V loaded three tiles ahead, half the L2 -> LDS traffic per FLOP; needs N
-                             to be a multiple of 256 and d <= 128                                       */
+                             K/V loaded three tiles ahead, half the L2 -> LDS traffic per FLOP, no barrier
+                             in the loop (the wavefronts count arrivals in LDS with one tile of slack);
+                             needs N to be a multiple of 256 and d <= 128.  FA2_VARIANT_AUTO takes it at
+                             d = 128, N >= 2048 when its workgroups fill whole rounds of the CUs          */
 };
 
 /*

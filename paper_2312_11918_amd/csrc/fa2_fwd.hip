@@ -43,6 +43,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kBr = 32 * kWaves;     // query rows per workgroup (32 per wavefront)
 constexpr int kBc = 64;              // keys per K/V tile
 constexpr int kSpinLimit = 1 << 18;  // polls of the arrival count before a wavefront gives up (tens of milliseconds)
+constexpr int kCUs = 256;            // compute units of the whole chip (tile-shape choice only)
 constexpr int kXcds = 8;             // accelerator complex dies; workgroup i is dispatched to XCD i % 8
 constexpr float kLazyLog2 = 8.0f;    // the rowmax reference moves only when exceeded by 2^8
 
@@ -725,13 +726,18 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if ((unsigned long long)n_max * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32))
     return FA2_ERR_UNSUPPORTED;
   if (variant == FA2_VARIANT_AUTO) {
-    // Measured on MI355X with N(0,1) inputs, the 4-wavefront, 128-row shape with block-wise softmax is the
-    // fastest on every workload shape tried (N = 512 .. 16384, d = 64 and 128); the others stay selectable
-    // for sweeps.
-    variant = FA2_VARIANT_NARROW;
+    // Measured on MI355X with N(0,1) inputs: the 8-wavefront, 256-row shape is 1-4 % faster than the 4-wavefront,
+    // 128-row shape at d = 128 from N = 2048 on, provided its workgroups (one per CU at a time) fill whole rounds
+    // of the chip's 256 CUs or are many; with a partial round the 128-row shape, two workgroups per CU, spreads
+    // the remainder better.  Everywhere else (d = 64, d = 256, short or masked or partial-tile problems) the
+    // 128-row shape is the faster or the only one.
+    const long long wg256 = (long long)B * H * (Nq / kRows256);
+    const bool rows256 = d == 128 && mask == FA2_MASK_NONE && Nq == Nk && Nq % kRows256 == 0 && Nq >= 2048 &&
+                         (wg256 % kCUs == 0 || wg256 >= 16 * kCUs);
+    variant = rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {
-    // the 256-row shape exists for tile-shape sweeps: whole tiles, square, unmasked, d <= 128
+    // the 256-row shape: whole tiles, square, unmasked, d <= 128
     if (Nq != Nk || Nq % kRows256 != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
