@@ -689,9 +689,10 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   const long long total_ll = (long long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);
   if (total_ll > 0x7fffffffLL) return FA2_ERR_UNSUPPORTED;
   const int total = (int)total_ll;
-  if (rows256) {  // exact tiles, no mask, d <= 128 (checked by the caller)
+  if (rows256) {  // exact tiles, d <= 128 (checked by the caller)
     if constexpr (D <= 128) {
-      return launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+      return causal ? launch_rows32<DT, D, 8, 4, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
+                    : launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
     } else {
       return FA2_ERR_UNSUPPORTED;
     }
@@ -731,14 +732,17 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
     // of the chip's 256 CUs or are many; with a partial round the 128-row shape, two workgroups per CU, spreads
     // the remainder better.  Everywhere else (d = 64, d = 256, short or masked or partial-tile problems) the
     // 128-row shape is the faster or the only one.
-    const long long wg256 = (long long)B * H * (Nq / kRows256);
-    const bool rows256 = d == 128 && mask == FA2_MASK_NONE && Nq == Nk && Nq % kRows256 == 0 && Nq >= 2048 &&
+    // Under the causal mask (one workgroup per pair of Q tiles) the gain starts at N = 8192.
+    const bool causal = mask == FA2_MASK_CAUSAL;
+    const long long qt256 = Nq / kRows256;
+    const long long wg256 = (long long)B * H * (causal ? (qt256 + 1) / 2 : qt256);
+    const bool rows256 = d == 128 && Nq == Nk && Nq % kRows256 == 0 && Nq >= (causal ? 8192 : 2048) &&
                          (wg256 % kCUs == 0 || wg256 >= 16 * kCUs);
     variant = rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {
-    // the 256-row shape: whole tiles, square, unmasked, d <= 128
-    if (Nq != Nk || Nq % kRows256 != 0 || mask != FA2_MASK_NONE || d == 256) return FA2_ERR_UNSUPPORTED;
+    // the 256-row shape: whole tiles, square, d <= 128
+    if (Nq != Nk || Nq % kRows256 != 0 || d == 256) return FA2_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == FA2_FP16) {
