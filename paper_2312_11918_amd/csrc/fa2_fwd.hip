@@ -159,7 +159,7 @@ template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
 __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_fwd_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ LSE, int H, int Nq, int Nk, float scale_log2e, int n_qtiles,
-    int total_tiles) {
+    int total_tiles, int chain) {
   using E = Elem<DT>;
   using T = Tile<D>;
   using std::false_type;
@@ -181,6 +181,10 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // start the two wavefronts of every SIMD in the same phase tile after tile, softmax against softmax and MFMAs
   // against MFMAs; with a tile of slack they drift apart and fill each other's gaps.
   constexpr bool kFlagSync = kWv == 8;
+  // Without a mask a workgroup of that shape takes `chain` consecutive Q tiles of one head, and the K/V stream runs
+  // on from one to the next (tile n_tiles + t is tile t again): only the first Q tile pays for filling the ring,
+  // and with one workgroup per CU nothing else would cover that time.  n_qtiles is a multiple of chain.
+  constexpr bool kChain = kFlagSync && !kCausal;
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
   // buffer cannot alias the operand reads from another.  (With kNBuf == 2 the last two pairs are unused.)
@@ -213,12 +217,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Under the causal mask the work of Q tile qt grows like qt + 1, so a workgroup takes a PAIR of Q tiles of
   // one head, n_qtiles-1-p and then p, one after the other: every workgroup then does the same amount of
   // work (but for the unpaired middle tile when n_qtiles is odd).  total_tiles counts pairs in that case.
-  const int n_items = kCausal ? (n_qtiles + 1) / 2 : n_qtiles;
+  const int n_items = kCausal ? (n_qtiles + 1) / 2 : kChain ? n_qtiles / chain : n_qtiles;
   const int bh = tile / n_items;
-  const int item = tile - bh * n_items;
+  const int item = kChain ? (tile - bh * n_items) * chain : tile - bh * n_items;   // (first) Q tile or pair
   const int b = bh / H;
   const int h = bh - b * H;
-  const int n_pass = (kCausal && item != n_qtiles - 1 - item) ? 2 : 1;
+  const int n_pass = kChain ? chain : (kCausal && item != n_qtiles - 1 - item) ? 2 : 1;
   int qt, q_row, n_tiles;  // set per pass
 
   const size_t row_stride = (size_t)H * D;                          // elements between consecutive tokens
@@ -522,6 +526,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   uint16_t* const k_buf[4] = {k_lds0, k_lds1, k_lds2, k_lds3};
   uint16_t* const v_buf[4] = {v_lds0, v_lds1, v_lds2, v_lds3};
 
+  int stream_base = 0;  // kChain: K/V tiles streamed for the Q tiles this workgroup has finished
+  bool more = false;    // kChain: another Q tile follows, so the stream goes on past tile n_tiles - 1
   // end of iteration j: publish what iteration j+1 reads, then refill the two dead buffers
   auto boundary = [&](auto relaxed_tag, int j, uint16_t* k_fill, uint16_t* v_fill) __attribute__((always_inline)) {
     if constexpr (kFlagSync) {
@@ -535,10 +541,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       // reached kWv * ((j-1)/4 + 1).  The wait is bounded: a wavefront that gives up poisons its rowsum, so the
       // error shows in O and LSE instead of hanging the GPU.
       // a first look at the others' count, under way while this wavefront waits for its own loads
+      // (with chained Q tiles the iterations are counted along the whole stream: n_tiles is a multiple of 4)
+      const int g = stream_base + j;
       uint32_t seen = __hip_atomic_load(&arrivals[(j + 3) & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       __builtin_amdgcn_s_waitcnt(kWaitAll);
       if (lane == 0) __hip_atomic_fetch_add(&arrivals[j & 3], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-      const uint32_t target = j > 0 ? (uint32_t)(kWv * ((j - 1) / 4 + 1)) : 0u;
+      const uint32_t target = g > 0 ? (uint32_t)(kWv * ((g - 1) / 4 + 1)) : 0u;
       int spins = 0;
       while (seen < target) {
         __builtin_amdgcn_s_sleep(1);
@@ -550,8 +558,11 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the tiles are read only after the count was seen
       hurry = spins == 0;
-      if (j + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, j + kNBuf, k_fill);
-      if (j - 1 + kNBuf < n_tiles) stage_in(false_type{}, v_rsrc, j - 1 + kNBuf, v_fill);
+      const int kt = j + kNBuf, vt = j - 1 + kNBuf;
+      if (kt < n_tiles) stage_in(true_type{}, k_rsrc, kt, k_fill);
+      else if (more) stage_in(true_type{}, k_rsrc, kt - n_tiles, k_fill);
+      if (vt < n_tiles) stage_in(false_type{}, v_rsrc, vt, v_fill);
+      else if (more) stage_in(false_type{}, v_rsrc, vt - n_tiles, v_fill);
       return;
     }
     if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
@@ -565,17 +576,25 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // buffers refilled at the boundary after iteration j+i of a group of kNBuf iterations (see `boundary`)
   constexpr int kKFillShift = kFlagSync ? 0 : 1, kVFillShift = kFlagSync ? kNBuf - 1 : 0;
 
+  // Q fragment of Q tile `qtile`: B operand of S^T = K Q^T, straight from global memory into registers
+  auto load_q = [&](int qtile) __attribute__((always_inline)) {
+    const int row = qtile * kRows + wave * 32 + r;
+    const int row_ld = kRagged ? min(row, Nq - 1) : row;
+    const uint16_t* qp = Q + head_base + (size_t)row_ld * row_stride + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+  };
+
   for (int pass = 0; pass < n_pass; ++pass) {
-    if (pass > 0) __syncthreads();  // the first Q tile's last K/V reads are over before the buffers are refilled
-    qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
+    // causal pair: the first Q tile's last K/V reads are over before the buffers are refilled
+    if (pass > 0 && !kChain) __syncthreads();
+    qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : kChain ? item + pass : item;
     q_row = qt * kRows + wave * 32 + r;
     // a multiple of kNBuf in every case; causal: the keys up to the end of this Q tile
     n_tiles = kCausal ? (qt + 1) * kNBuf : kRagged ? (Nk + kNBuf * kBc - 1) / (kNBuf * kBc) * kNBuf : Nk / kBc;
-    {
-      const int q_row_ld = kRagged ? min(q_row, Nq - 1) : q_row;
-      const uint16_t* qp = Q + head_base + (size_t)q_row_ld * row_stride + 8 * hh;
-#pragma unroll
-      for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+    if constexpr (kChain) {
+      stream_base = pass * n_tiles;
+      more = pass + 1 < n_pass;
     }
 #pragma unroll
     for (int db = 0; db < kDBlocks; ++db)
@@ -585,15 +604,18 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     mc_ref = -INFINITY;
     l_run = 0.f;
 
-    static_for<kNBuf>([&](auto t) { stage_in(true_type{}, k_rsrc, decltype(t)::value, k_buf[decltype(t)::value]); });
-    static_for<kNBuf - 1>([&](auto t) { stage_in(false_type{}, v_rsrc, decltype(t)::value, v_buf[decltype(t)::value]); });
-    // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
+    // A chained Q tile after the first finds its ring filled, its Q fragment loaded and its first S computed by
+    // the end of the pass before it.
+    if (!kChain || pass == 0) {
+      load_q(qt);
+      static_for<kNBuf>([&](auto t) { stage_in(true_type{}, k_rsrc, decltype(t)::value, k_buf[decltype(t)::value]); });
+      static_for<kNBuf - 1>([&](auto t) { stage_in(false_type{}, v_rsrc, decltype(t)::value, v_buf[decltype(t)::value]); });
+      // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
 #pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
-    __builtin_amdgcn_s_waitcnt(kWaitAll);
-    if (kFlagSync && tid < 4) arrivals[tid] = 0;
-    __syncthreads();
-    {
+      for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+      __builtin_amdgcn_s_waitcnt(kWaitAll);
+      if (kFlagSync && tid < 4) arrivals[tid] = 0;
+      __syncthreads();
       gemm1(k_lds0);
       __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
       if constexpr (!kFlagSync) {   // (with kFlagSync the first boundary issues these two)
@@ -628,7 +650,19 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
         iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
       } else {
+        // Q is last used by the GEMM-I of the iteration before this one: the next Q tile's fragment is fetched
+        // under this iteration
+        if (kChain && more) load_q(qt + 1);
         iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
+        if (kChain && more) {
+          // S of the next Q tile's first K/V tile (stream tile n_tiles, complete since the boundary two iterations
+          // ago), then the boundary that every iteration of the stream ends with.  O, l and the reference of this
+          // Q tile are untouched by both and are written out below.
+#pragma unroll
+          for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+          gemm1(k_buf[(i + 1) % kNBuf]);
+          boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
+        }
       }
     });
 
@@ -670,11 +704,13 @@ int enqueue(void (*kernel)(Params...), int grid, int block, hipStream_t stream, 
 // One instantiation of the 32-row kernel.
 template <int DT, int D, int kWv, int kNBuf, bool kCausal, bool kRagged>
 int launch_rows32(const void* Q, const void* K, const void* V, void* O, float* LSE, int H, int Nq, int Nk,
-                  float scale_log2e, int n_qtiles, int total, hipStream_t stream) {
+                  float scale_log2e, int n_qtiles, int total, hipStream_t stream, int chain = 1) {
   return enqueue(fa2_fwd_kernel<DT, D, kWv, kNBuf, kCausal, kRagged>, total, kWv * 64, stream,
                  static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V),
-                 static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles, total);
+                 static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, chain);
 }
+
+int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
 
 template <int DT, int D>
 int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, float scale,
@@ -691,8 +727,13 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   const int total = (int)total_ll;
   if (rows256) {  // exact tiles, d <= 128 (checked by the caller)
     if constexpr (D <= 128) {
-      return causal ? launch_rows32<DT, D, 8, 4, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
-                    : launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+      if (causal)
+        return launch_rows32<DT, D, 8, 4, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+      // Unmasked: when the Q tiles fill whole rounds of the CUs, a workgroup takes `chain` consecutive Q tiles of a
+      // head (as many as divide both the rounds and the head's Q tiles), so that fewer workgroups fill their ring.
+      const int chain = total % kCUs == 0 ? gcd(n_qtiles, total / kCUs) : 1;
+      return launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total / chain,
+                                                      stream, chain);
     } else {
       return FA2_ERR_UNSUPPORTED;
     }
