@@ -181,9 +181,11 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // start the two wavefronts of every SIMD in the same phase tile after tile, softmax against softmax and MFMAs
   // against MFMAs; with a tile of slack they drift apart and fill each other's gaps.
   constexpr bool kFlagSync = kWv == 8;
-  // Without a mask a workgroup of that shape takes `chain` consecutive Q tiles of one head, and the K/V stream runs
-  // on from one to the next (tile n_tiles + t is tile t again): only the first Q tile pays for filling the ring,
-  // and with one workgroup per CU nothing else would cover that time.  n_qtiles is a multiple of chain.
+  // Without a mask a workgroup of that shape takes `chain` Q tiles one after the other, and the K/V stream runs on
+  // from one to the next (after the last K/V tile of one comes the first of the next): only the first Q tile pays
+  // for filling the ring, and with one workgroup per CU nothing else would cover that time.  The Q tiles of a
+  // workgroup are spaced by the number of workgroups of its XCD, so that at any time the workgroups of an XCD
+  // work on neighbouring Q tiles, a few heads whose K and V fit its L2, as they do without chaining.
   constexpr bool kChain = kFlagSync && !kCausal;
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
@@ -207,28 +209,34 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Q-tile scheduling (Algorithm 2's outer loop, parallel over workgroups).  Workgroups are dealt
   // round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous range of tiles so
   // that the Q tiles of one head, which all stream the same K and V, share one L2.
-  int tile;
+  int tile, chain_stride = 0;  // kChain: the Q tile of pass c is tile + c * chain_stride, counted over all heads
   {
     const int wg = blockIdx.x;
     const int per = total_tiles / kXcds, rem = total_tiles % kXcds;
     const int xcd = wg % kXcds, idx = wg / kXcds;
-    tile = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    const int first = xcd * per + (xcd < rem ? xcd : rem);  // first workgroup of this XCD's range
+    if constexpr (kChain) {
+      tile = first * chain + idx;
+      chain_stride = per + (xcd < rem ? 1 : 0);
+    } else {
+      tile = first + idx;
+    }
   }
   // Under the causal mask the work of Q tile qt grows like qt + 1, so a workgroup takes a PAIR of Q tiles of
   // one head, n_qtiles-1-p and then p, one after the other: every workgroup then does the same amount of
   // work (but for the unpaired middle tile when n_qtiles is odd).  total_tiles counts pairs in that case.
-  const int n_items = kCausal ? (n_qtiles + 1) / 2 : kChain ? n_qtiles / chain : n_qtiles;
-  const int bh = tile / n_items;
-  const int item = kChain ? (tile - bh * n_items) * chain : tile - bh * n_items;   // (first) Q tile or pair
-  const int b = bh / H;
-  const int h = bh - b * H;
+  const int n_items = kCausal ? (n_qtiles + 1) / 2 : n_qtiles;
+  int bh = tile / n_items;                // batch entry * H + head (kChain: of the current pass)
+  const int item = tile - bh * n_items;   // Q tile, or pair of Q tiles (kChain: first Q tile)
   const int n_pass = kChain ? chain : (kCausal && item != n_qtiles - 1 - item) ? 2 : 1;
   int qt, q_row, n_tiles;  // set per pass
 
   const size_t row_stride = (size_t)H * D;                          // elements between consecutive tokens
-  const size_t head_base = ((size_t)b * Nq * H + (size_t)h) * D;    // element (b, 0, h, 0) of Q and O
-  const size_t kv_head_base = ((size_t)b * Nk * H + (size_t)h) * D; // element (b, 0, h, 0) of K and V
   const size_t tile_stride = (size_t)kBc * row_stride;              // elements between consecutive K/V tiles
+  // element (b, 0, h, 0) of Q and O / of K and V, for head index bh = b * H + h
+  auto q_base_of = [&](int bh_) { return ((size_t)(bh_ / H) * Nq * H + (size_t)(bh_ % H)) * D; };
+  auto kv_base_of = [&](int bh_) { return ((size_t)(bh_ / H) * Nk * H + (size_t)(bh_ % H)) * D; };
+  size_t head_base = q_base_of(bh);
 
   // Q_i fragment, held in registers for the whole loop: B operand of S^T = K Q^T.
   u32x4 qf[kKSteps];
@@ -240,10 +248,15 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // descriptor, a scalar tile offset and the 32-bit per-lane offset, and its range check turns any
   // offset past the last row into zeros instead of a fault.
   const uint32_t head_bytes = (uint32_t)(((size_t)(Nk - 1) * row_stride + D) * 2);
-  const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(K + kv_head_base), 0, (int)head_bytes, kBufferFlags);
-  const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(V + kv_head_base), 0, (int)head_bytes, kBufferFlags);
+  auto rsrc_of = [&](const uint16_t* tensor, int bh_) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(tensor + kv_base_of(bh_)), 0, (int)head_bytes,
+                                             kBufferFlags);
+  };
+  __amdgpu_buffer_rsrc_t k_rsrc = rsrc_of(K, bh), v_rsrc = rsrc_of(V, bh);
+  // kChain: the head and Q tile of the next pass, whose first K/V tiles the last boundaries of this pass load
+  __amdgpu_buffer_rsrc_t k_rsrc_next = k_rsrc, v_rsrc_next = v_rsrc;
+  size_t head_base_next = head_base;
+  int qt_next = 0;
   const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
   const uint32_t row_bytes = (uint32_t)(row_stride * 2);
   // is_k is a compile-time tag: K and V tiles use different chunk swizzles.  The per-lane source offsets are
@@ -560,9 +573,9 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       hurry = spins == 0;
       const int kt = j + kNBuf, vt = j - 1 + kNBuf;
       if (kt < n_tiles) stage_in(true_type{}, k_rsrc, kt, k_fill);
-      else if (more) stage_in(true_type{}, k_rsrc, kt - n_tiles, k_fill);
+      else if (more) stage_in(true_type{}, k_rsrc_next, kt - n_tiles, k_fill);
       if (vt < n_tiles) stage_in(false_type{}, v_rsrc, vt, v_fill);
-      else if (more) stage_in(false_type{}, v_rsrc, vt - n_tiles, v_fill);
+      else if (more) stage_in(false_type{}, v_rsrc_next, vt - n_tiles, v_fill);
       return;
     }
     if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
@@ -577,10 +590,10 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   constexpr int kKFillShift = kFlagSync ? 0 : 1, kVFillShift = kFlagSync ? kNBuf - 1 : 0;
 
   // Q fragment of Q tile `qtile`: B operand of S^T = K Q^T, straight from global memory into registers
-  auto load_q = [&](int qtile) __attribute__((always_inline)) {
+  auto load_q = [&](size_t base, int qtile) __attribute__((always_inline)) {
     const int row = qtile * kRows + wave * 32 + r;
     const int row_ld = kRagged ? min(row, Nq - 1) : row;
-    const uint16_t* qp = Q + head_base + (size_t)row_ld * row_stride + 8 * hh;
+    const uint16_t* qp = Q + base + (size_t)row_ld * row_stride + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
   };
@@ -588,14 +601,28 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   for (int pass = 0; pass < n_pass; ++pass) {
     // causal pair: the first Q tile's last K/V reads are over before the buffers are refilled
     if (pass > 0 && !kChain) __syncthreads();
-    qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : kChain ? item + pass : item;
+    if constexpr (kChain) {
+      const int t = tile + pass * chain_stride;
+      bh = t / n_qtiles;
+      qt = t - bh * n_qtiles;
+      head_base = q_base_of(bh);
+      k_rsrc = rsrc_of(K, bh);
+      v_rsrc = rsrc_of(V, bh);
+      more = pass + 1 < n_pass;
+      if (more) {
+        const int bh_next = (t + chain_stride) / n_qtiles;
+        qt_next = t + chain_stride - bh_next * n_qtiles;
+        head_base_next = q_base_of(bh_next);
+        k_rsrc_next = rsrc_of(K, bh_next);
+        v_rsrc_next = rsrc_of(V, bh_next);
+      }
+    } else {
+      qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
+    }
     q_row = qt * kRows + wave * 32 + r;
     // a multiple of kNBuf in every case; causal: the keys up to the end of this Q tile
     n_tiles = kCausal ? (qt + 1) * kNBuf : kRagged ? (Nk + kNBuf * kBc - 1) / (kNBuf * kBc) * kNBuf : Nk / kBc;
-    if constexpr (kChain) {
-      stream_base = pass * n_tiles;
-      more = pass + 1 < n_pass;
-    }
+    if constexpr (kChain) stream_base = pass * n_tiles;
 #pragma unroll
     for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
@@ -607,7 +634,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     // A chained Q tile after the first finds its ring filled, its Q fragment loaded and its first S computed by
     // the end of the pass before it.
     if (!kChain || pass == 0) {
-      load_q(qt);
+      load_q(head_base, qt);
       static_for<kNBuf>([&](auto t) { stage_in(true_type{}, k_rsrc, decltype(t)::value, k_buf[decltype(t)::value]); });
       static_for<kNBuf - 1>([&](auto t) { stage_in(false_type{}, v_rsrc, decltype(t)::value, v_buf[decltype(t)::value]); });
       // The Q fragment must have landed before the loop so that no wait for it is placed inside the loop.
@@ -652,7 +679,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       } else {
         // Q is last used by the GEMM-I of the iteration before this one: the next Q tile's fragment is fetched
         // under this iteration
-        if (kChain && more) load_q(qt + 1);
+        if (kChain && more) load_q(head_base_next, qt_next);
         iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         if (kChain && more) {
           // S of the next Q tile's first K/V tile (stream tile n_tiles, complete since the boundary two iterations
@@ -682,7 +709,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
         }
       }
       if (LSE != nullptr && hh == 0) {
-        LSE[((size_t)b * H + h) * Nq + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
+        LSE[(size_t)bh * Nq + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
       }
     }
   }  // pass
@@ -710,7 +737,6 @@ int launch_rows32(const void* Q, const void* K, const void* V, void* O, float* L
                  static_cast<uint16_t*>(O), LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, chain);
 }
 
-int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
 
 template <int DT, int D>
 int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, float scale,
@@ -729,9 +755,8 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
     if constexpr (D <= 128) {
       if (causal)
         return launch_rows32<DT, D, 8, 4, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
-      // Unmasked: when the Q tiles fill whole rounds of the CUs, a workgroup takes `chain` consecutive Q tiles of a
-      // head (as many as divide both the rounds and the head's Q tiles), so that fewer workgroups fill their ring.
-      const int chain = total % kCUs == 0 ? gcd(n_qtiles, total / kCUs) : 1;
+      // Unmasked: when the Q tiles fill whole rounds of the CUs, one workgroup per CU takes a Q tile of every round.
+      const int chain = total % kCUs == 0 ? total / kCUs : 1;
       return launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total / chain,
                                                       stream, chain);
     } else {
