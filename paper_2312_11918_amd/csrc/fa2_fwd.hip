@@ -199,6 +199,9 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds2[kNBuf == 4 ? T::kElems : 8];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds3[kNBuf == 4 ? T::kElems : 8];
   __shared__ uint32_t arrivals[4];  // kFlagSync: wavefronts that finished iteration j, counted in entry j % 4
+  // kFlagSync: 32 rows x 32 columns of O per wavefront, through which the result is turned from one query per
+  // lane into whole 64-byte pieces of rows before it is stored
+  __shared__ __attribute__((aligned(16))) uint16_t o_slab[kFlagSync ? kWv * 1024 : 8];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -697,6 +700,32 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     const float l_tot = sum_with_partner_half(l_run);
     const float inv_l = 1.0f / l_tot;
     if (!kRagged || q_row < Nq) {
+      if constexpr (kFlagSync) {
+        // With one workgroup per CU nothing hides the store instructions: a lane-per-query store touches 64 rows
+        // per instruction.  Each 32-column block goes through the wavefront's own LDS slab instead (row r at
+        // byte 64 r, its four 16-byte chunks XOR-permuted by (r / 4) % 4 against bank conflicts) and leaves as
+        // two stores of 16 rows x 64 bytes.  Only this wavefront touches its slab, and LDS executes a wavefront's
+        // accesses in order, so no barrier is involved.
+        uint16_t* slab = o_slab + wave * 1024;
+        const int rrow = lane >> 2, rchunk = lane & 3;   // as a reader: row (+16 for the second half), chunk
+        uint16_t* orow = O + head_base + (size_t)(qt * kRows + wave * 32 + rrow) * row_stride + 8 * rchunk;
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            // accumulator registers 4g..4g+3 hold d = 32 db + 8 g + 4 hh + (0..3) of this lane's query
+            u32x2 w = {E::pack2(ot[db][4 * g + 0] * inv_l, ot[db][4 * g + 1] * inv_l),
+                       E::pack2(ot[db][4 * g + 2] * inv_l, ot[db][4 * g + 3] * inv_l)};
+            *reinterpret_cast<u32x2*>(slab + r * 32 + 8 * (g ^ ((r >> 2) & 3)) + 4 * hh) = w;
+          }
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const int row = rrow + 16 * half;
+            const u32x4 piece = *reinterpret_cast<const u32x4*>(slab + row * 32 + 8 * (rchunk ^ ((row >> 2) & 3)));
+            *reinterpret_cast<u32x4*>(orow + (size_t)(16 * half) * row_stride + 32 * db) = piece;
+          }
+        }
+      } else {
       uint16_t* op = O + head_base + (size_t)q_row * row_stride + 4 * hh;
 #pragma unroll
       for (int db = 0; db < kDBlocks; ++db) {
@@ -707,6 +736,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
                      E::pack2(ot[db][4 * g + 2] * inv_l, ot[db][4 * g + 3] * inv_l)};
           *reinterpret_cast<u32x2*>(op + db * 32 + g * 8) = w;
         }
+      }
       }
       if (LSE != nullptr && hh == 0) {
         LSE[(size_t)bh * Nq + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
@@ -793,17 +823,19 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if ((unsigned long long)n_max * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32))
     return FA2_ERR_UNSUPPORTED;
   if (variant == FA2_VARIANT_AUTO) {
-    // Measured on MI355X with N(0,1) inputs: the 8-wavefront, 256-row shape is 1-4 % faster than the 4-wavefront,
-    // 128-row shape at d = 128 from N = 2048 on, provided its workgroups (one per CU at a time) fill whole rounds
-    // of the chip's 256 CUs or are many; with a partial round the 128-row shape, two workgroups per CU, spreads
-    // the remainder better.  Everywhere else (d = 64, d = 256, short or masked or partial-tile problems) the
+    // Measured on MI355X with N(0,1) inputs: the 8-wavefront, 256-row shape is 3-7 % faster than the 4-wavefront,
+    // 128-row shape at d = 128 from N = 512 on, provided its Q tiles (one workgroup per CU at a time) fill whole
+    // rounds of the chip's 256 CUs, or from N = 2048 on when they are many; with a partial round the 128-row
+    // shape, two workgroups per CU, spreads the remainder better.  Everywhere else (d = 64, d = 256, short or masked or partial-tile problems) the
     // 128-row shape is the faster or the only one.
     // Under the causal mask (one workgroup per pair of Q tiles) the gain starts at N = 8192.
     const bool causal = mask == FA2_MASK_CAUSAL;
     const long long qt256 = Nq / kRows256;
     const long long wg256 = (long long)B * H * (causal ? (qt256 + 1) / 2 : qt256);
-    const bool rows256 = d == 128 && Nq == Nk && Nq % kRows256 == 0 && Nq >= (causal ? 8192 : 2048) &&
-                         (wg256 % kCUs == 0 || wg256 >= 16 * kCUs);
+    const bool whole_rounds = wg256 % kCUs == 0;   // unmasked: then one workgroup per CU chains a Q tile of every round
+    const bool rows256 = d == 128 && Nq == Nk && Nq % kRows256 == 0 &&
+                         (causal ? Nq >= 8192 && (whole_rounds || wg256 >= 16 * kCUs)
+                                 : (whole_rounds && Nq >= 512) || (wg256 >= 16 * kCUs && Nq >= 2048));
     variant = rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {
