@@ -823,19 +823,19 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if ((unsigned long long)n_max * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32))
     return FA2_ERR_UNSUPPORTED;
   if (variant == FA2_VARIANT_AUTO) {
-    // Measured on MI355X with N(0,1) inputs: the 8-wavefront, 256-row shape is 3-7 % faster than the 4-wavefront,
-    // 128-row shape at d = 128 from N = 512 on, provided its Q tiles (one workgroup per CU at a time) fill whole
-    // rounds of the chip's 256 CUs, or from N = 2048 on when they are many; with a partial round the 128-row
-    // shape, two workgroups per CU, spreads the remainder better.  Everywhere else (d = 64, d = 256, short or masked or partial-tile problems) the
-    // 128-row shape is the faster or the only one.
+    // Measured on MI355X with N(0,1) inputs: when its Q tiles fill whole rounds of the chip's 256 CUs (one workgroup
+    // per CU, which then takes one Q tile of every round), the 8-wavefront, 256-row shape is faster than the
+    // 4-wavefront, 128-row shape at every N: by 4-19 % at d = 128 (most at N = 512), by 1-4 % at d = 64.  With many
+    // rounds that are not whole it still gains at d = 128 from N = 2048 on; with few, the 128-row shape, two
+    // workgroups per CU, spreads the remainder better.  d = 256 and partial tiles exist in the 128-row shape only.
     // Under the causal mask (one workgroup per pair of Q tiles) the gain starts at N = 8192.
     const bool causal = mask == FA2_MASK_CAUSAL;
     const long long qt256 = Nq / kRows256;
     const long long wg256 = (long long)B * H * (causal ? (qt256 + 1) / 2 : qt256);
     const bool whole_rounds = wg256 % kCUs == 0;   // unmasked: then one workgroup per CU chains a Q tile of every round
-    const bool rows256 = d == 128 && Nq == Nk && Nq % kRows256 == 0 &&
-                         (causal ? Nq >= 8192 && (whole_rounds || wg256 >= 16 * kCUs)
-                                 : (whole_rounds && Nq >= 512) || (wg256 >= 16 * kCUs && Nq >= 2048));
+    const bool rows256 = d <= 128 && Nq == Nk && Nq % kRows256 == 0 &&
+                         (causal ? d == 128 && Nq >= 8192 && (whole_rounds || wg256 >= 16 * kCUs)
+                                 : whole_rounds || (d == 128 && wg256 >= 16 * kCUs && Nq >= 2048));
     variant = rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {

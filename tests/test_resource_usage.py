@@ -14,8 +14,8 @@ def kernels():
 def test_every_instantiation_is_reported(kernels):
     names = {k["name"] for k in kernels}
     # 2 element types x (3 head dimensions x 4 mask/partial-tile combinations of the 128-row shape
-    #                    + 2 head dimensions of the 256-row shape)
-    assert len(names) == 2 * (3 * 4 + 2), sorted(names)
+    #                    + 2 head dimensions x with and without the causal mask of the 256-row shape)
+    assert len(names) == 2 * (3 * 4 + 2 * 2), sorted(names)
 
 
 def test_no_kernel_uses_scratch_memory(kernels):
