@@ -16,7 +16,7 @@ import sys
 import numpy as np
 
 VARIANTS = [("128 query rows x 64 keys (4 wavefronts x 32 rows, 2 workgroups/CU)", 1),
-            ("256 query rows x 64 keys (8 wavefronts x 32 rows, 1 workgroup/CU)", 3)]
+            ("256 query rows x 64 keys (8 wavefronts x 32 rows, 1 workgroup/CU, chained Q tiles)", 3)]
 PEAK = 2516.6
 
 
