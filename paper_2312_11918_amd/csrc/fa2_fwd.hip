@@ -16,8 +16,9 @@
 //  * V is the operand whose contraction index (the key) is not contiguous in memory (Section 4.1
 //    of the paper takes a transposed shared-memory view).  Here V stays row-major in LDS and is
 //    read with ds_read_b64_tr_b16, the LDS transpose load of gfx950.
-//  * K/V tiles are double-buffered in LDS and the next tile's global loads are issued before the
-//    current tile's MFMAs (the copy/GEMM overlap of Section 6, without TMA or mbarriers).
+//  * K/V tiles are double-buffered (or held in a ring of four) in LDS and the next tiles' global loads are
+//    issued before the current tile's MFMAs (the copy/GEMM overlap of Section 6, without TMA or mbarriers;
+//    the producer/consumer hand-over is a barrier per tile in one tile shape and counters in LDS in the other).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -141,8 +142,11 @@ constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3 for gf
 // cycle through kNBuf LDS buffers each.  Two shapes are instantiated:
 //   4 wavefronts, 2 buffers: 128 rows per workgroup, 2 workgroups per CU;
 //   8 wavefronts, 4 buffers: 256 rows per workgroup, 1 workgroup per CU, global loads issued three
-//                            tiles ahead and half the L2->LDS traffic per FLOP.
+//                            tiles ahead and half the L2->LDS traffic per FLOP.  This shape has no barrier in
+//                            its loop (arrival counters in LDS, see kFlagSync), takes `chain` Q tiles per
+//                            workgroup over one running K/V stream (see kChain) and stores O as pieces of rows.
 // Either way a SIMD runs two wavefronts, so one wavefront's softmax arithmetic overlaps the other's MFMAs.
+// `total_tiles` is the number of workgroups; `chain` is 1 except for unmasked launches of the 8-wavefront shape.
 //
 // kCausal applies the optional mask of S (Section 2 of the paper: entries of S may be set to -inf before the
 // softmax; here those with key index > query index).  A Q tile then stops at its diagonal: it visits
