@@ -203,9 +203,10 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds2[kNBuf == 4 ? T::kElems : 8];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds3[kNBuf == 4 ? T::kElems : 8];
   __shared__ uint32_t arrivals[4];  // kFlagSync: wavefronts that finished iteration j, counted in entry j % 4
-  // kFlagSync: 32 rows x 32 columns of O per wavefront, through which the result is turned from one query per
+  // kRowStores: 32 rows x 32 columns of O per wavefront, through which the result is turned from one query per
   // lane into whole 64-byte pieces of rows before it is stored
-  __shared__ __attribute__((aligned(16))) uint16_t o_slab[kFlagSync ? kWv * 1024 : 8];
+  constexpr bool kRowStores = kFlagSync || (D == 256 && !kRagged);  // shapes with one workgroup per CU
+  __shared__ __attribute__((aligned(16))) uint16_t o_slab[kRowStores ? kWv * 1024 : 8];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -704,7 +705,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     const float l_tot = sum_with_partner_half(l_run);
     const float inv_l = 1.0f / l_tot;
     if (!kRagged || q_row < Nq) {
-      if constexpr (kFlagSync) {
+      if constexpr (kRowStores) {
         // With one workgroup per CU nothing hides the store instructions: a lane-per-query store touches 64 rows
         // per instruction.  Each 32-column block goes through the wavefront's own LDS slab instead (row r at
         // byte 64 r, its four 16-byte chunks XOR-permuted by (r / 4) % 4 against bank conflicts) and leaves as
