@@ -185,12 +185,13 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // start the two wavefronts of every SIMD in the same phase tile after tile, softmax against softmax and MFMAs
   // against MFMAs; with a tile of slack they drift apart and fill each other's gaps.
   constexpr bool kFlagSync = kWv == 8;
-  // Without a mask a workgroup of that shape takes `chain` Q tiles one after the other, and the K/V stream runs on
+  // A workgroup of that shape takes `chain` Q tiles (under the causal mask: pairs of Q tiles, and the two of a
+  // pair as well) one after the other, and the K/V stream runs on
   // from one to the next (after the last K/V tile of one comes the first of the next): only the first Q tile pays
   // for filling the ring, and with one workgroup per CU nothing else would cover that time.  The Q tiles of a
   // workgroup are spaced by the number of workgroups of its XCD, so that at any time the workgroups of an XCD
   // work on neighbouring Q tiles, a few heads whose K and V fit its L2, as they do without chaining.
-  constexpr bool kChain = kFlagSync && !kCausal;
+  constexpr bool kChain = kFlagSync;
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
   // buffer cannot alias the operand reads from another.  (With kNBuf == 2 the last two pairs are unused.)
@@ -217,7 +218,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // Q-tile scheduling (Algorithm 2's outer loop, parallel over workgroups).  Workgroups are dealt
   // round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous range of tiles so
   // that the Q tiles of one head, which all stream the same K and V, share one L2.
-  int tile, chain_stride = 0;  // kChain: the Q tile of pass c is tile + c * chain_stride, counted over all heads
+  int tile, chain_stride = 0;  // kChain: the Q tile (pair) of chain step c is tile + c * chain_stride, over all heads
   {
     const int wg = blockIdx.x;
     const int per = total_tiles / kXcds, rem = total_tiles % kXcds;
@@ -236,7 +237,9 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   const int n_items = kCausal ? (n_qtiles + 1) / 2 : n_qtiles;
   int bh = tile / n_items;                // batch entry * H + head (kChain: of the current pass)
   const int item = tile - bh * n_items;   // Q tile, or pair of Q tiles (kChain: first Q tile)
-  const int n_pass = kChain ? chain : (kCausal && item != n_qtiles - 1 - item) ? 2 : 1;
+  // passes of this workgroup: Q tiles it works through.  A chain longer than 1 under the causal mask is only
+  // launched when every pair is complete (n_qtiles even).
+  const int n_pass = kCausal ? (chain > 1 ? 2 * chain : item != n_qtiles - 1 - item ? 2 : 1) : kChain ? chain : 1;
   int qt, q_row, n_tiles;  // set per pass
 
   const size_t row_stride = (size_t)H * D;                          // elements between consecutive tokens
@@ -262,9 +265,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   };
   __amdgpu_buffer_rsrc_t k_rsrc = rsrc_of(K, bh), v_rsrc = rsrc_of(V, bh);
   // kChain: the head and Q tile of the next pass, whose first K/V tiles the last boundaries of this pass load
-  __amdgpu_buffer_rsrc_t k_rsrc_next = k_rsrc, v_rsrc_next = v_rsrc;
-  size_t head_base_next = head_base;
-  int qt_next = 0;
+  // (their descriptors are made where they are used, not kept in scalar registers through the loop)
+  int bh_next = 0, qt_next = 0;
   const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
   const uint32_t row_bytes = (uint32_t)(row_stride * 2);
   // is_k is a compile-time tag: K and V tiles use different chunk swizzles.  The per-lane source offsets are
@@ -581,9 +583,9 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       hurry = spins == 0;
       const int kt = j + kNBuf, vt = j - 1 + kNBuf;
       if (kt < n_tiles) stage_in(true_type{}, k_rsrc, kt, k_fill);
-      else if (more) stage_in(true_type{}, k_rsrc_next, kt - n_tiles, k_fill);
+      else if (more) stage_in(true_type{}, rsrc_of(K, bh_next), kt - n_tiles, k_fill);
       if (vt < n_tiles) stage_in(false_type{}, v_rsrc, vt, v_fill);
-      else if (more) stage_in(false_type{}, v_rsrc_next, vt - n_tiles, v_fill);
+      else if (more) stage_in(false_type{}, rsrc_of(V, bh_next), vt - n_tiles, v_fill);
       return;
     }
     if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
@@ -606,31 +608,31 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
   };
 
+  // the arrival counters start at zero; the first pass's barrier publishes them
+  if (kFlagSync && tid < 4) arrivals[tid] = 0;
   for (int pass = 0; pass < n_pass; ++pass) {
     // causal pair: the first Q tile's last K/V reads are over before the buffers are refilled
     if (pass > 0 && !kChain) __syncthreads();
     if constexpr (kChain) {
-      const int t = tile + pass * chain_stride;
-      bh = t / n_qtiles;
-      qt = t - bh * n_qtiles;
+      // head and Q tile of pass p: chain step p (causal: p / 2, the heavy tile of the pair first, then the light one)
+      auto locate = [&](int p, int& bh_, int& qt_) {
+        const int t = tile + (kCausal ? p >> 1 : p) * chain_stride;
+        bh_ = t / n_items;
+        const int it = t - bh_ * n_items;
+        qt_ = kCausal ? ((p & 1) == 0 ? n_qtiles - 1 - it : it) : it;
+      };
+      locate(pass, bh, qt);
       head_base = q_base_of(bh);
       k_rsrc = rsrc_of(K, bh);
       v_rsrc = rsrc_of(V, bh);
       more = pass + 1 < n_pass;
-      if (more) {
-        const int bh_next = (t + chain_stride) / n_qtiles;
-        qt_next = t + chain_stride - bh_next * n_qtiles;
-        head_base_next = q_base_of(bh_next);
-        k_rsrc_next = rsrc_of(K, bh_next);
-        v_rsrc_next = rsrc_of(V, bh_next);
-      }
+      if (more) locate(pass + 1, bh_next, qt_next);
     } else {
       qt = kCausal ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
     }
     q_row = qt * kRows + wave * 32 + r;
     // a multiple of kNBuf in every case; causal: the keys up to the end of this Q tile
     n_tiles = kCausal ? (qt + 1) * kNBuf : kRagged ? (Nk + kNBuf * kBc - 1) / (kNBuf * kBc) * kNBuf : Nk / kBc;
-    if constexpr (kChain) stream_base = pass * n_tiles;
 #pragma unroll
     for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
@@ -649,7 +651,6 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
 #pragma unroll
       for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
       __builtin_amdgcn_s_waitcnt(kWaitAll);
-      if (kFlagSync && tid < 4) arrivals[tid] = 0;
       __syncthreads();
       gemm1(k_lds0);
       __syncthreads();  // every wavefront has finished reading K tile 0 before its buffer is refilled
@@ -687,7 +688,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       } else {
         // Q is last used by the GEMM-I of the iteration before this one: the next Q tile's fragment is fetched
         // under this iteration
-        if (kChain && more) load_q(head_base_next, qt_next);
+        if (kChain && more) load_q(q_base_of(bh_next), qt_next);
         iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         if (kChain && more) {
           // S of the next Q tile's first K/V tile (stream tile n_tiles, complete since the boundary two iterations
@@ -747,6 +748,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
         LSE[(size_t)bh * Nq + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
       }
     }
+    if constexpr (kChain) stream_base += n_tiles;  // every pass's tile count is a multiple of kNBuf
   }  // pass
 }
 
@@ -788,10 +790,12 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
   const int total = (int)total_ll;
   if (rows256) {  // exact tiles, d <= 128 (checked by the caller)
     if constexpr (D <= 128) {
+      // When the Q tiles (causal: the pairs of Q tiles, all complete) fill whole rounds of the CUs, one workgroup
+      // per CU takes a Q tile (pair) of every round.
+      const int chain = total % kCUs == 0 && !(causal && n_qtiles % 2 != 0) ? total / kCUs : 1;
       if (causal)
-        return launch_rows32<DT, D, 8, 4, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
-      // Unmasked: when the Q tiles fill whole rounds of the CUs, one workgroup per CU takes a Q tile of every round.
-      const int chain = total % kCUs == 0 ? total / kCUs : 1;
+        return launch_rows32<DT, D, 8, 4, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total / chain,
+                                                       stream, chain);
       return launch_rows32<DT, D, 8, 4, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total / chain,
                                                       stream, chain);
     } else {

@@ -27,6 +27,8 @@ def _run_gpu(qb, kb, vb, dtype, scale, causal=True, bits=False):
     (3, 1, 1024, 128, "fp16", 0.0),
     (1, 2, 384, 256, "fp16", 0.0),    # d = 256
     (2, 1, 512, 256, "bf16", 0.0),
+    (16, 16, 2304, 128, "fp16", 0.0),  # 256-row shape: 9 Q tiles per head, the middle one unpaired (no chain)
+    (4, 16, 4096, 128, "bf16", 0.0),   # 256-row shape: 512 pairs, every workgroup chains two of them
 ])
 def test_causal_parity_elementwise(B, H, N, d, dtype, outliers):
     seed = 3000 + 5 * N + d + B
