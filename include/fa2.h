@@ -78,8 +78,11 @@ enum {
   FA2_VARIANT_NARROW8 = 3 /* 256 query rows per workgroup (8 wavefronts x 32 rows), 1 workgroup per CU,
                              K/V loaded three tiles ahead, half the L2 -> LDS traffic per FLOP, no barrier
                              in the loop (the wavefronts count arrivals in LDS with one tile of slack);
-                             needs N to be a multiple of 256 and d <= 128.  FA2_VARIANT_AUTO takes it at
-                             d = 128, N >= 2048 when its workgroups fill whole rounds of the CUs          */
+                             when the Q tiles fill whole rounds of the CUs a workgroup takes one of every
+                             round over one running K/V stream; needs N to be a multiple of 256 and
+                             d <= 128.  FA2_VARIANT_AUTO takes it when the Q tiles fill whole rounds of
+                             the 256 CUs (d = 128 also with very many tiles, and under the causal mask
+                             from N = 2048 on) and the 128-row shape otherwise                          */
 };
 
 /*
