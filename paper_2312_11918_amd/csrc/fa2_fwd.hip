@@ -894,4 +894,4 @@ extern "C" const char* fa2_strerror(int code) {
   }
 }
 
-extern "C" int fa2_version(void) { return 400; /* 0.4.0 */ }
+extern "C" int fa2_version(void) { return 500; /* 0.5.0 */ }

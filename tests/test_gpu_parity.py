@@ -134,20 +134,27 @@ def test_parity_full_size_workloads(index):
 
 def test_256_row_shape_repeats_bit_for_bit():
     # The 8-wavefront shape synchronises through arrival counters in LDS instead of barriers: a tile read before it
-    # was complete, or overwritten while still in use, would show as launches that differ.  Thirty launches of the
-    # headline shape (which the library runs in this shape) and of a shape with the outlier keys must give
-    # identical bits, and equal the explicit choice of the shape.
+    # was complete, or overwritten while still in use, would show as launches that differ.  Thirty launches each of
+    # the headline shape, of a bf16 shape with outlier keys, of workload 2's shape (chains that change head at every
+    # Q tile) and of the headline shape under the causal mask (chained pairs) must give identical bits; where the
+    # shape can be named explicitly, the library's own choice must equal it.
     torch = torch_gpu()
-    for B, H, N, d, dtype, outliers in [(8, 16, 2048, 128, "fp16", 0.0), (2, 16, 4096, 128, "bf16", 0.01)]:
-        print(f"repeat B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    for B, H, N, d, dtype, outliers, causal in [(8, 16, 2048, 128, "fp16", 0.0, False),
+                                                (2, 16, 4096, 128, "bf16", 0.01, False),
+                                                (32, 16, 512, 64, "fp16", 0.0, False),
+                                                (8, 16, 2048, 128, "fp16", 0.0, True)]:
+        print(f"repeat B={B} H={H} N={N} d={d} {dtype} causal={causal}", flush=True)
         qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, 777, k_outlier_frac=outliers, k_outlier_gain=8.0)
         scale = float(np.float32(d) ** np.float32(-0.5))
         q, k, v = (to_device(x, dtype) for x in (qb, kb, vb))
-        first = fa2.fa2_fwd(q, k, v, scale, variant=fa2.FA2_VARIANT_NARROW8)
+        if causal:
+            first = fa2.fa2_fwd(q, k, v, scale, causal=True)
+        else:
+            first = fa2.fa2_fwd(q, k, v, scale, variant=fa2.FA2_VARIANT_NARROW8)
         torch.cuda.synchronize()
         assert bool(torch.isfinite(first[0]).all()) and bool(torch.isfinite(first[1]).all())
         for n in range(30):
-            o, lse = fa2.fa2_fwd(q, k, v, scale)
+            o, lse = fa2.fa2_fwd(q, k, v, scale, causal=causal)
             assert torch.equal(o, first[0]) and torch.equal(lse, first[1]), f"launch {n} differs"
 
 
