@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   __shared__ uint32_t arrivals[4];  // kFlagSync: wavefronts that finished iteration j, counted in entry j % 4
   // kRowStores: 32 rows x 32 columns of O per wavefront, through which the result is turned from one query per
   // lane into whole 64-byte pieces of rows before it is stored
-  constexpr bool kRowStores = kFlagSync || (D == 256 && !kRagged);  // shapes with one workgroup per CU
+  constexpr bool kRowStores = kFlagSync || D == 256;  // shapes with one workgroup per CU
   __shared__ __attribute__((aligned(16))) uint16_t o_slab[kRowStores ? kWv * 1024 : 8];
 
   const int tid = threadIdx.x;
@@ -705,7 +705,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     // Epilogue: O_i = O_i / rowsum, LSE_i = m_i + ln(rowsum) (natural log, scaled logits).
     const float l_tot = sum_with_partner_half(l_run);
     const float inv_l = 1.0f / l_tot;
-    if (!kRagged || q_row < Nq) {
+    if (kRowStores || !kRagged || q_row < Nq) {   // (row stores: every lane takes part, rows are checked one by one)
       if constexpr (kRowStores) {
         // With one workgroup per CU nothing hides the store instructions: a lane-per-query store touches 64 rows
         // per instruction.  Each 32-column block goes through the wavefront's own LDS slab instead (row r at
@@ -728,7 +728,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
           for (int half = 0; half < 2; ++half) {
             const int row = rrow + 16 * half;
             const u32x4 piece = *reinterpret_cast<const u32x4*>(slab + row * 32 + 8 * (rchunk ^ ((row >> 2) & 3)));
-            *reinterpret_cast<u32x4*>(orow + (size_t)(16 * half) * row_stride + 32 * db) = piece;
+            if (!kRagged || qt * kRows + wave * 32 + row < Nq)
+              *reinterpret_cast<u32x4*>(orow + (size_t)(16 * half) * row_stride + 32 * db) = piece;
           }
         }
       } else {
@@ -744,7 +745,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
         }
       }
       }
-      if (LSE != nullptr && hh == 0) {
+      if (LSE != nullptr && hh == 0 && (!kRagged || q_row < Nq)) {
         LSE[(size_t)bh * Nq + q_row] = mc_ref * 0.69314718055994530942f + __builtin_logf(l_tot);
       }
     }
