@@ -205,8 +205,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds3[kNBuf == 4 ? T::kElems : 8];
   __shared__ uint32_t arrivals[4];  // kFlagSync: wavefronts that finished iteration j, counted in entry j % 4
   // kRowStores: 32 rows x 32 columns of O per wavefront, through which the result is turned from one query per
-  // lane into whole 64-byte pieces of rows before it is stored
-  constexpr bool kRowStores = kFlagSync || D == 256;  // shapes with one workgroup per CU
+  // lane into whole 64-byte pieces of rows before it is stored: a lane-per-query store touches 64 rows per
+  // instruction, and the epilogue of a Q tile then costs thousands of cycles that only partly hide behind the other
+  // workgroups of the CU (measured: +2 % at N = 2048, +5...10 % at N <= 1024, more with one workgroup per CU)
+  // (every kernel but one: the 128-row shape at d = 128 with both the causal mask and partial tiles has no
+  // registers left for it)
+  constexpr bool kRowStores = !(kWv == 4 && D == 128 && kCausal && kRagged);
   __shared__ __attribute__((aligned(16))) uint16_t o_slab[kRowStores ? kWv * 1024 : 8];
 
   const int tid = threadIdx.x;
@@ -707,8 +711,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     const float inv_l = 1.0f / l_tot;
     if (kRowStores || !kRagged || q_row < Nq) {   // (row stores: every lane takes part, rows are checked one by one)
       if constexpr (kRowStores) {
-        // With one workgroup per CU nothing hides the store instructions: a lane-per-query store touches 64 rows
-        // per instruction.  Each 32-column block goes through the wavefront's own LDS slab instead (row r at
+        // Each 32-column block goes through the wavefront's own LDS slab (row r at
         // byte 64 r, its four 16-byte chunks XOR-permuted by (r / 4) % 4 against bank conflicts) and leaves as
         // two stores of 16 rows x 64 bytes.  Only this wavefront touches its slab, and LDS executes a wavefront's
         // accesses in order, so no barrier is involved.
