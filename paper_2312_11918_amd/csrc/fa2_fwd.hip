@@ -838,9 +838,10 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   if (variant == FA2_VARIANT_AUTO) {
     // Measured on MI355X with N(0,1) inputs: when its Q tiles fill whole rounds of the chip's 256 CUs (one workgroup
     // per CU, which then takes one Q tile of every round), the 8-wavefront, 256-row shape is faster than the
-    // 4-wavefront, 128-row shape at every N: by 4-19 % at d = 128 (most at N = 512), by 1-4 % at d = 64.  With many
-    // rounds that are not whole it still gains at d = 128 from N = 2048 on; with few, the 128-row shape, two
-    // workgroups per CU, spreads the remainder better.  d = 256 and partial tiles exist in the 128-row shape only.
+    // 4-wavefront, 128-row shape by 3-6 % at d = 128 at every N, and by 1-2 % at d = 64 from N = 4096 on (at d = 64
+    // below N = 2048 its two wavefronts per SIMD against three lose 2-5 %).  With many rounds that are not whole it
+    // still gains at d = 128 from N = 2048 on; with few, the 128-row shape, two workgroups per CU, spreads the
+    // remainder better.  d = 256 and partial tiles exist in the 128-row shape only.
     // Under the causal mask (one workgroup per pair of Q tiles, no chaining) it gains 1-3 % at d = 128 from N = 2048 on.
     const bool causal = mask == FA2_MASK_CAUSAL;
     const long long qt256 = Nq / kRows256;
@@ -848,7 +849,8 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
     const bool whole_rounds = wg256 % kCUs == 0;   // unmasked: then one workgroup per CU chains a Q tile of every round
     const bool rows256 = d <= 128 && Nq == Nk && Nq % kRows256 == 0 &&
                          (causal ? d == 128 && Nq >= 2048 && (whole_rounds || wg256 >= 16 * kCUs)
-                                 : whole_rounds || (d == 128 && wg256 >= 16 * kCUs && Nq >= 2048));
+                                 : (whole_rounds && (d == 128 || Nq >= 2048)) ||
+                                       (d == 128 && wg256 >= 16 * kCUs && Nq >= 2048));
     variant = rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
   }
   if (variant != FA2_VARIANT_NARROW) {
