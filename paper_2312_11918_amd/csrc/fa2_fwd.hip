@@ -540,11 +540,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   };
 
   // LDS schedule.  K tile t lives in k_lds[t % kNBuf], V tile t in v_lds[t % kNBuf].  Iteration j reads
-  // V tile j and K tile j+1 and ends with the one barrier per tile; after that barrier those two tiles are
-  // dead and their buffers are refilled with K tile j+1+kNBuf and V tile j+kNBuf.  The loads needed by
-  // iteration j+1 (K tile j+2, V tile j+1) were issued kNBuf-1 barriers earlier; every barrier issues
-  // 2*kLoadsPerWave loads per wavefront, so while every barrier issues its full set it is enough to wait
-  // until at most (kNBuf-2)*2*kLoadsPerWave loads are outstanding.
+  // V tile j and K tile j+1.  With a barrier per tile (4-wavefront kernels) those two tiles are dead after the
+  // barrier that ends the iteration, and their buffers are refilled with K tile j+1+kNBuf and V tile j+kNBuf;
+  // the loads needed by iteration j+1 (K tile j+2, V tile j+1) were issued kNBuf-1 barriers earlier; every
+  // barrier issues 2*kLoadsPerWave loads per wavefront, so while every barrier issues its full set it is enough
+  // to wait until at most (kNBuf-2)*2*kLoadsPerWave loads are outstanding.  Without barriers (kFlagSync) the
+  // refill is one tile behind that, see `boundary`.
   constexpr int kRelaxedVmcnt = (kNBuf - 2) * 2 * kLoadsPerWave;
   static_assert(kRelaxedVmcnt < 64, "vmcnt is a 6-bit counter");
   constexpr int kWaitRelaxed = (kRelaxedVmcnt & 15) | ((kRelaxedVmcnt >> 4) << 14) | 0x0F70;
