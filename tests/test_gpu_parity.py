@@ -45,6 +45,7 @@ def test_parity_elementwise(B, H, N, d, dtype):
     (1, 1, 1280, 128, "fp16"),    # n_tiles = 20
     (4, 64, 512, 64, "fp16"),     # 512 wide tiles = 2 rounds of the CUs: chains of 2, each over two heads
     (3, 64, 1024, 128, "bf16"),   # 768 wide tiles: chains of 3 that start anywhere in a head of 4 tiles
+    (8, 64, 256, 128, "fp16"),    # 512 wide tiles of only 4 K/V tiles each: chains of 2 with no main-loop trip
 ])
 def test_parity_explicit_variants(B, H, N, d, dtype, variant):
     seed = 2000 + 3 * N + d + B
