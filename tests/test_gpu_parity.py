@@ -234,12 +234,14 @@ def test_runs_on_a_side_stream_and_is_deterministic():
     assert torch.equal(o0, o1) and torch.equal(l0, l1)
 
 
-def test_launch_can_be_captured_in_a_hip_graph_and_replayed():
+@pytest.mark.parametrize("B,H,N,d,causal", [(2, 3, 384, 128, True),      # 128-row kernel, causal, partial Q tile count
+                                              (1, 64, 1024, 128, False)])  # 256-row kernel: LDS counters, chained
+def test_launch_can_be_captured_in_a_hip_graph_and_replayed(B, H, N, d, causal):
     # fa2_fwd only enqueues a kernel, so a stream capture records it; every replay must equal an eager launch on
-    # the inputs that are in the buffers at that time.  (Nothing but the kernel is captured: no memset, no copy.)
+    # the inputs that are in the buffers at that time.  (Nothing but the kernel is captured: no memset, no copy;
+    # the 256-row kernel clears its arrival counters itself, in LDS.)
     torch = torch_gpu()
-    B, H, N, d = 2, 3, 384, 128
-    print("graph capture and replay", flush=True)
+    print(f"graph capture and replay B={B} H={H} N={N} d={d} causal={causal}", flush=True)
     q, k, v = (torch.empty((B, N, H, d), dtype=torch.float16, device="cuda") for _ in range(3))
     o = torch.empty_like(q)
     lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
@@ -254,16 +256,16 @@ def test_launch_can_be_captured_in_a_hip_graph_and_replayed():
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
-        fa2.fa2_fwd(q, k, v, 0.1, out=o, lse=lse, causal=True)
+        fa2.fa2_fwd(q, k, v, 0.1, out=o, lse=lse, causal=causal)
     for seed in (51, 52, 53):
         qb, kb, vb = fill(seed)
         o.fill_(float("nan"))
         g.replay()
         torch.cuda.synchronize()
-        o_eager, lse_eager = fa2.fa2_fwd(q, k, v, 0.1, causal=True)
+        o_eager, lse_eager = fa2.fa2_fwd(q, k, v, 0.1, causal=causal)
         torch.cuda.synchronize()
         assert torch.equal(o, o_eager) and torch.equal(lse, lse_eager), f"replay with seed {seed} differs from eager"
-        o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), 0.1, causal=True)
+        o_ref, lse_ref = oracle.attention(*(oracle.widen(x, "fp16") for x in (qb, kb, vb)), 0.1, causal=causal)
         check(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, f"graph replay seed {seed}")
 
 
@@ -320,7 +322,8 @@ def test_concurrent_launches_from_threads_on_their_own_streams():
     torch = torch_gpu()
     print("concurrent launches", flush=True)
     shapes = [(2, 3, 512, 128, "fp16", False), (1, 4, 1000, 64, "bf16", False), (2, 2, 640, 128, "fp16", True),
-              (1, 2, 768, 256, "fp16", False)]
+              (1, 2, 768, 256, "fp16", False),
+              (1, 64, 1024, 128, "fp16", False)]   # runs in the 256-row shape (256 Q tiles: one round, LDS counters)
     jobs = []
     for i, (B, H, N, d, dtype, causal) in enumerate(shapes):
         qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, 700 + i)
