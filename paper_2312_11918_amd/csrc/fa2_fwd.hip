@@ -687,14 +687,18 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       // computed here, not hoisted above the main loop where 32 comparison results per tile would sit in
       // scalar registers for the whole loop
       if constexpr (mask_tail::value) asm volatile("" : "+v"(visible));
+      // Under the causal mask a tile of the Q tile's own rows lies wholly above the diagonal for the wavefronts whose
+      // 32 rows come before its first key: for them it would contribute exact zeros, so they leave its arithmetic
+      // out (and keep every boundary: the others still count on their loads and arrivals).
+      const bool live = !kCausal || i * kBc <= wave * 32 + 31;   // wavefront-uniform
       if constexpr (i + 1 < kNBuf) {
-        iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
+        if (live) iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
       } else {
         // Q is last used by the GEMM-I of the iteration before this one: the next Q tile's fragment is fetched
         // under this iteration
         if (kChain && more) load_q(q_base_of(bh_next), qt_next);
-        iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
+        if (live) iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         if (kChain && more) {
           // S of the next Q tile's first K/V tile (stream tile n_tiles, complete since the boundary two iterations
           // ago), then the boundary that every iteration of the stream ends with.  O, l and the reference of this
