@@ -689,8 +689,9 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       if constexpr (mask_tail::value) asm volatile("" : "+v"(visible));
       // Under the causal mask a tile of the Q tile's own rows lies wholly above the diagonal for the wavefronts whose
       // 32 rows come before its first key: for them it would contribute exact zeros, so they leave its arithmetic
-      // out (and keep every boundary: the others still count on their loads and arrivals).
-      const bool live = !kCausal || i * kBc <= wave * 32 + 31;   // wavefront-uniform
+      // out (and keep every boundary: the others still count on their loads and arrivals).  The same goes, for every
+      // wavefront, for a padding tile that only rounds the tile count up and holds no key at all.
+      const bool live = (!kCausal || i * kBc <= wave * 32 + 31) && (!kRagged || (j + i) * kBc < Nk);   // uniform
       if constexpr (i + 1 < kNBuf) {
         if (live) iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
