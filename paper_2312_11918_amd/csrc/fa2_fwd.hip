@@ -667,11 +667,15 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       }
     }
 
+    // partial tiles: wavefronts whose rows all lie past the last query keep the boundaries and skip the arithmetic
+    // (not in the two partial-tile kernels that have no register left for one more condition)
+    constexpr bool kSkipDeadRows = kRagged && D <= 128 && !(D == 128 && kCausal);
+    const bool rows_live = !kSkipDeadRows || qt * kRows + wave * 32 < Nq;   // wavefront-uniform
     int j = 0;
     for (; j + kNBuf < n_tiles; j += kNBuf) {  // every barrier of these iterations issues its full set of loads
       static_for<kNBuf>([&](auto t) {
         constexpr int i = decltype(t)::value;
-        iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
+        if (rows_live) iteration(true_type{}, false_type{}, 0, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(true_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
       });
     }
@@ -691,7 +695,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       // 32 rows come before its first key: for them it would contribute exact zeros, so they leave its arithmetic
       // out (and keep every boundary: the others still count on their loads and arrivals).  The same goes, for every
       // wavefront, for a padding tile that only rounds the tile count up and holds no key at all.
-      const bool live = (!kCausal || i * kBc <= wave * 32 + 31) && (!kRagged || (j + i) * kBc < Nk);   // uniform
+      // And a wavefront whose 32 rows all lie past the last query (partial last Q tile) computes nothing at all.
+      const bool live = (!kCausal || i * kBc <= wave * 32 + 31) && (!kRagged || (j + i) * kBc < Nk) && rows_live;
       if constexpr (i + 1 < kNBuf) {
         if (live) iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
         boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
