@@ -39,8 +39,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;            // wavefronts per workgroup
-constexpr int kThreads = kWaves * 64;
+constexpr int kWaves = 4;            // wavefronts per workgroup of the 128-row shape
 constexpr int kBr = 32 * kWaves;     // query rows per workgroup (32 per wavefront)
 constexpr int kBc = 64;              // keys per K/V tile
 constexpr int kSpinLimit = 1 << 18;  // polls of the arrival count before a wavefront gives up (tens of milliseconds)
@@ -81,11 +80,6 @@ template <> struct Elem<FA2_BF16> {
 
 // Value held by the partner lane (l ^ 32): v_permlane32_swap exchanges the upper half of one
 // register with the lower half of another, which leaves each half's value broadcast in one result.
-__device__ __forceinline__ float max_with_partner_half(float x) {
-  uint32_t u = __builtin_bit_cast(uint32_t, x);
-  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
-}
 __device__ __forceinline__ float sum_with_partner_half(float x) {
   uint32_t u = __builtin_bit_cast(uint32_t, x);
   auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
