@@ -185,7 +185,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // for filling the ring, and with one workgroup per CU nothing else would cover that time.  The Q tiles of a
   // workgroup are spaced by the number of workgroups of its XCD, so that at any time the workgroups of an XCD
   // work on neighbouring Q tiles, a few heads whose K and V fit its L2, as they do without chaining.
-  constexpr bool kChain = kFlagSync;
+  // The d = 256 kernel, also one workgroup per CU, chains in the same way when it runs without a mask on whole tiles.
+  constexpr bool kChain = kFlagSync || (kWv == 4 && D == 256 && !kCausal && !kRagged);
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
   // buffer cannot alias the operand reads from another.  (With kNBuf == 2 the last two pairs are unused.)
@@ -265,6 +266,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // kChain: the head and Q tile of the next pass, whose first K/V tiles the last boundaries of this pass load
   // (their descriptors are made where they are used, not kept in scalar registers through the loop)
   int bh_next = 0, qt_next = 0;
+  int stream_base = 0;  // kChain: K/V tiles streamed for the Q tiles this workgroup has finished
+  bool more = false;    // kChain: another Q tile follows, so the stream goes on past tile n_tiles - 1
   const uint32_t tile_bytes = (uint32_t)(tile_stride * 2);
   const uint32_t row_bytes = (uint32_t)(row_stride * 2);
   // is_k is a compile-time tag: K and V tiles use different chunk swizzles.  The per-lane source offsets are
@@ -436,6 +439,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     auto stage_ahead = [&]() __attribute__((always_inline)) {
       if constexpr (kSplitRefill) {
         if (jj + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, jj + kNBuf, k_refill);
+        else if (kChain && more) stage_in(true_type{}, rsrc_of(K, bh_next), jj + kNBuf - n_tiles, k_refill);
       }
 #pragma unroll
       for (int i = 0; i < kRing; ++i) ring[i] = v_frag(v_cur, i);
@@ -548,8 +552,6 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   uint16_t* const k_buf[4] = {k_lds0, k_lds1, k_lds2, k_lds3};
   uint16_t* const v_buf[4] = {v_lds0, v_lds1, v_lds2, v_lds3};
 
-  int stream_base = 0;  // kChain: K/V tiles streamed for the Q tiles this workgroup has finished
-  bool more = false;    // kChain: another Q tile follows, so the stream goes on past tile n_tiles - 1
   // end of iteration j: publish what iteration j+1 reads, then refill the two dead buffers
   auto boundary = [&](auto relaxed_tag, int j, uint16_t* k_fill, uint16_t* v_fill) __attribute__((always_inline)) {
     if constexpr (kFlagSync) {
@@ -590,10 +592,13 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     if constexpr (decltype(relaxed_tag)::value) __builtin_amdgcn_s_waitcnt(kWaitRelaxed);
     else __builtin_amdgcn_s_waitcnt(kWaitAll);
     __syncthreads();
+    // (a chained pass that another one follows goes on with that one's first tiles)
     if constexpr (!kSplitRefill) {
       if (j + 1 + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, j + 1 + kNBuf, k_fill);
+      else if (kChain && more) stage_in(true_type{}, rsrc_of(K, bh_next), j + 1 + kNBuf - n_tiles, k_fill);
     }
     if (j + kNBuf < n_tiles) stage_in(false_type{}, v_rsrc, j + kNBuf, v_fill);
+    else if (kChain && more) stage_in(false_type{}, rsrc_of(V, bh_next), j + kNBuf - n_tiles, v_fill);
   };
   // buffers refilled at the boundary after iteration j+i of a group of kNBuf iterations (see `boundary`)
   constexpr int kKFillShift = kFlagSync ? 0 : 1, kVFillShift = kFlagSync ? kNBuf - 1 : 0;
@@ -814,8 +819,12 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
     return ragged ? launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
                   : launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
   }
-  return ragged ? launch_rows32<DT, D, 4, 2, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
-                : launch_rows32<DT, D, 4, 2, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+  if (ragged) return launch_rows32<DT, D, 4, 2, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+  // d = 256 (one workgroup per CU): when the Q tiles fill whole rounds of the CUs, one workgroup per CU takes a Q tile
+  // of every round, as in the 256-row shape
+  const int chain = D == 256 && total % kCUs == 0 ? total / kCUs : 1;
+  return launch_rows32<DT, D, 4, 2, false, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total / chain, stream,
+                                                  chain);
 }
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
