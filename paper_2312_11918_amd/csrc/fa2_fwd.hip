@@ -185,8 +185,8 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // for filling the ring, and with one workgroup per CU nothing else would cover that time.  The Q tiles of a
   // workgroup are spaced by the number of workgroups of its XCD, so that at any time the workgroups of an XCD
   // work on neighbouring Q tiles, a few heads whose K and V fit its L2, as they do without chaining.
-  // The d = 256 kernel, also one workgroup per CU, chains in the same way when it runs without a mask on whole tiles.
-  constexpr bool kChain = kFlagSync || (kWv == 4 && D == 256 && !kCausal && !kRagged);
+  // The d = 256 kernel, also one workgroup per CU, chains in the same way when it runs on whole tiles.
+  constexpr bool kChain = kFlagSync || (kWv == 4 && D == 256 && !kRagged);
 
   // The buffers are separate objects on purpose: the compiler then knows that a load in flight into one
   // buffer cannot alias the operand reads from another.  (With kNBuf == 2 the last two pairs are unused.)
@@ -368,6 +368,12 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
   // 32 kb + 8 (v/4) + v%4 (the key's position in the tile minus this half's 4 hh) that register v of key
   // block kb may have for its key to be at or before this lane's query.
   bool hurry = false;  // kFlagSync: this wavefront did not have to wait at its last boundary, so it is among the slowest
+  // kSplitRefill: the K half of the refill, issued inside iteration jj (see stage_ahead there): K tile jj + kNBuf,
+  // or, past the end of a chained pass that another one follows, that one's tile
+  auto split_k_refill = [&](int jj, uint16_t* k_refill) __attribute__((always_inline)) {
+    if (jj + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, jj + kNBuf, k_refill);
+    else if (kChain && more) stage_in(true_type{}, rsrc_of(K, bh_next), jj + kNBuf - n_tiles, k_refill);
+  };
   auto iteration = [&](auto next_tag, auto mask_tag, int visible, const uint16_t* v_cur, const uint16_t* k_next,
                        int jj, uint16_t* k_refill) __attribute__((always_inline)) {
     if constexpr (decltype(mask_tag)::value) {
@@ -437,10 +443,7 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
     //    stands still meanwhile;
     //  * the first V fragments of GEMM-II: independent of P~, so their LDS latency hides behind the exponentials.
     auto stage_ahead = [&]() __attribute__((always_inline)) {
-      if constexpr (kSplitRefill) {
-        if (jj + kNBuf < n_tiles) stage_in(true_type{}, k_rsrc, jj + kNBuf, k_refill);
-        else if (kChain && more) stage_in(true_type{}, rsrc_of(K, bh_next), jj + kNBuf - n_tiles, k_refill);
-      }
+      if constexpr (kSplitRefill) split_k_refill(jj, k_refill);
 #pragma unroll
       for (int i = 0; i < kRing; ++i) ring[i] = v_frag(v_cur, i);
     };
@@ -698,12 +701,14 @@ __global__ __launch_bounds__(kWv * 64, (kWv == 4 && D <= 128) ? 2 : 1) void fa2_
       const bool live = (!kCausal || i * kBc <= wave * 32 + 31) && (!kRagged || (j + i) * kBc < Nk) && rows_live;
       if constexpr (i + 1 < kNBuf) {
         if (live) iteration(true_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
+        else if constexpr (kSplitRefill) split_k_refill(j + i, k_buf[i]);   // its loads are still this wavefront's
         boundary(false_type{}, j + i, k_buf[(i + kKFillShift) % kNBuf], v_buf[(i + kVFillShift) % kNBuf]);
       } else {
         // Q is last used by the GEMM-I of the iteration before this one: the next Q tile's fragment is fetched
         // under this iteration
         if (kChain && more) load_q(q_base_of(bh_next), qt_next);
         if (live) iteration(false_type{}, mask_tail{}, visible, v_buf[i], k_buf[(i + 1) % kNBuf], j + i, k_buf[i]);
+        else if constexpr (kSplitRefill) split_k_refill(j + i, k_buf[i]);
         if (kChain && more) {
           // S of the next Q tile's first K/V tile (stream tile n_tiles, complete since the boundary two iterations
           // ago), then the boundary that every iteration of the stream ends with.  O, l and the reference of this
@@ -816,8 +821,11 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
       return FA2_ERR_UNSUPPORTED;
     }
   } else if (causal) {
-    return ragged ? launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream)
-                  : launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+    if (ragged) return launch_rows32<DT, D, 4, 2, true, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
+    // d = 256: pairs chained like the Q tiles of the unmasked case (whole rounds of complete pairs)
+    const int chain = D == 256 && total % kCUs == 0 && n_qtiles % 2 == 0 ? total / kCUs : 1;
+    return launch_rows32<DT, D, 4, 2, true, false>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total / chain, stream,
+                                                   chain);
   }
   if (ragged) return launch_rows32<DT, D, 4, 2, false, true>(Q, K, V, O, LSE, H, Nq, Nk, scale_log2e, n_qtiles, total, stream);
   // d = 256 (one workgroup per CU): when the Q tiles fill whole rounds of the CUs, one workgroup per CU takes a Q tile

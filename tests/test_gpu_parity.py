@@ -115,18 +115,22 @@ def test_parity_paper_shapes_sweep_variants(d, variant):
           f"paper shape d{d} variant {variant} ({len(rows)} rows, one per query tile)")
 
 
-@pytest.mark.parametrize("B,H,N,dtype", [(4, 64, 256, "fp16"),    # 512 Q tiles of 2 per head: chains of 2, a new head each
-                                           (2, 64, 768, "bf16")])   # 768 Q tiles of 6 per head: chains of 3
-def test_parity_d256_chained_q_tiles(B, H, N, dtype):
-    # d = 256 with whole rounds of the CUs: one workgroup per CU takes a Q tile of every round over one K/V stream
+@pytest.mark.parametrize("B,H,N,dtype,causal", [
+    (4, 64, 256, "fp16", False),    # 512 Q tiles of 2 per head: chains of 2, a new head each
+    (2, 64, 768, "bf16", False),    # 768 Q tiles of 6 per head: chains of 3
+    (8, 64, 256, "fp16", True),     # causal: 512 pairs, one per head: chains of 2 pairs
+    (1, 64, 1024, "fp16", True),    # causal: 256 pairs of 4 per head: one pair per workgroup, its two Q tiles chained
+])
+def test_parity_d256_chained_q_tiles(B, H, N, dtype, causal):
+    # d = 256 with whole rounds of the CUs: one workgroup per CU takes a Q tile (pair) of every round over one K/V stream
     d = 256
     seed = 2600 + N + B
-    print(f"d=256 chained case B={B} H={H} N={N} {dtype} seed={seed}", flush=True)
+    print(f"d=256 chained case B={B} H={H} N={N} {dtype} causal={causal} seed={seed}", flush=True)
     qb, kb, vb = workloads.make_qkv(B, N, H, d, dtype, seed)
     scale = float(np.float32(d) ** np.float32(-0.5))
-    o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale)
-    o, lse = run_gpu(qb, kb, vb, dtype, scale)
-    check(o, lse, o_ref, lse_ref, f"d=256 chained B{B} H{H} N{N} {dtype}")
+    o_ref, lse_ref = oracle.attention(*(oracle.widen(x, dtype) for x in (qb, kb, vb)), scale, causal=causal)
+    o, lse = run_gpu(qb, kb, vb, dtype, scale, causal=causal)
+    check(o, lse, o_ref, lse_ref, f"d=256 chained B{B} H{H} N{N} {dtype} causal={causal}")
 
 
 # ------------------------------------------------------------------ the full-size workloads, every element
