@@ -82,7 +82,9 @@ enum {
                              round over one running K/V stream; needs N to be a multiple of 256 and
                              d <= 128.  FA2_VARIANT_AUTO takes it when the Q tiles fill whole rounds of
                              the 256 CUs (d = 128 also with very many tiles, and under the causal mask
-                             from N = 2048 on) and the 128-row shape otherwise                          */
+                             from N = 2048 on) and the 128-row shape otherwise.  Its waits on the LDS
+                             counters are bounded (tens of milliseconds): should a wavefront ever give
+                             up, the rows it owns come out as NaN instead of the launch hanging         */
 };
 
 /*
