@@ -134,6 +134,14 @@ int fa2_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* 
 int fa2_fwd_qk(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, int d,
                float scale, int dtype, int mask, void* stream);
 
+/*
+ * fa2_tile_shape -- which tile shape (FA2_VARIANT_NARROW or FA2_VARIANT_NARROW8) the entry points without a
+ * `variant` argument use for a problem; the counterpart of reading the best cell off the paper's Table 1.  Host
+ * only: nothing is launched and no HIP call is made.  Returns the FA2_VARIANT_* value (> 0), or a negative
+ * FA2_ERR_* for sizes, head dimensions or masks that the entry points refuse.
+ */
+int fa2_tile_shape(int B, int H, int Nq, int Nk, int d, int mask);
+
 /* Static, NUL-terminated description of a return code (never NULL). */
 const char* fa2_strerror(int code);
 

@@ -57,6 +57,8 @@ def load_library():
         lib.fa2_fwd_qk.restype = ci
         lib.fa2_strerror.argtypes = [ci]
         lib.fa2_strerror.restype = ctypes.c_char_p
+        lib.fa2_tile_shape.argtypes = [ci, ci, ci, ci, ci, ci]
+        lib.fa2_tile_shape.restype = ci
         lib.fa2_version.argtypes = []
         lib.fa2_version.restype = ci
         _lib = lib
@@ -93,6 +95,11 @@ def fa2_probe_mfma_raw(operands_ptr, ticks_ptr, sink_ptr, dtype, iters, stream=N
 
 def fa2_strerror(code: int) -> str:
     return load_library().fa2_strerror(int(code)).decode()
+
+
+def fa2_tile_shape(B: int, H: int, Nq: int, Nk: int, d: int, mask: int = FA2_MASK_NONE) -> int:
+    """The tile shape (``FA2_VARIANT_*``) the library picks for a problem, or a negative error code.  No launch."""
+    return int(load_library().fa2_tile_shape(int(B), int(H), int(Nq), int(Nk), int(d), int(mask)))
 
 
 def fa2_version() -> int:

@@ -837,6 +837,26 @@ int launch(const void* Q, const void* K, const void* V, void* O, float* LSE, int
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// The tile shape that FA2_VARIANT_AUTO stands for (sizes already validated by the caller).
+int choose_variant(int B, int H, int Nq, int Nk, int d, int mask) {
+  // Measured on MI355X with N(0,1) inputs: when its Q tiles fill whole rounds of the chip's 256 CUs (one workgroup
+  // per CU, which then takes one Q tile of every round), the 8-wavefront, 256-row shape is faster than the
+  // 4-wavefront, 128-row shape by 3-6 % at d = 128 at every N, and by 1-2 % at d = 64 from N = 4096 on (at d = 64
+  // below N = 2048 its two wavefronts per SIMD against three lose 2-5 %).  With many rounds that are not whole it
+  // still gains at d = 128 from N = 2048 on; with few, the 128-row shape, two workgroups per CU, spreads the
+  // remainder better.  d = 256 and partial tiles exist in the 128-row shape only.
+  // Under the causal mask (one workgroup per pair of Q tiles, no chaining) it gains 1-3 % at d = 128 from N = 2048 on.
+  const bool causal = mask == FA2_MASK_CAUSAL;
+  const long long qt256 = Nq / kRows256;
+  const long long wg256 = (long long)B * H * (causal ? (qt256 + 1) / 2 : qt256);
+  const bool whole_rounds = wg256 % kCUs == 0;   // unmasked: then one workgroup per CU chains a Q tile of every round
+  const bool rows256 = d <= 128 && Nq == Nk && Nq % kRows256 == 0 &&
+                       (causal ? d == 128 && Nq >= 2048 && (whole_rounds || wg256 >= 16 * kCUs)
+                               : (whole_rounds && (d == 128 || Nq >= 2048)) ||
+                                     (d == 128 && wg256 >= 16 * kCUs && Nq >= 2048));
+  return rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
+}
+
 int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int Nq, int Nk, int d,
         float scale, int dtype, int variant, int mask, void* stream) {
   // All validation happens before the first HIP call: an error launches nothing.
@@ -857,24 +877,7 @@ int run(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
   // the K/V rows of one batch entry are addressed with 32-bit byte offsets from a buffer descriptor
   if ((unsigned long long)n_max * (unsigned long long)H * (unsigned long long)d * 2ull >= (1ull << 32))
     return FA2_ERR_UNSUPPORTED;
-  if (variant == FA2_VARIANT_AUTO) {
-    // Measured on MI355X with N(0,1) inputs: when its Q tiles fill whole rounds of the chip's 256 CUs (one workgroup
-    // per CU, which then takes one Q tile of every round), the 8-wavefront, 256-row shape is faster than the
-    // 4-wavefront, 128-row shape by 3-6 % at d = 128 at every N, and by 1-2 % at d = 64 from N = 4096 on (at d = 64
-    // below N = 2048 its two wavefronts per SIMD against three lose 2-5 %).  With many rounds that are not whole it
-    // still gains at d = 128 from N = 2048 on; with few, the 128-row shape, two workgroups per CU, spreads the
-    // remainder better.  d = 256 and partial tiles exist in the 128-row shape only.
-    // Under the causal mask (one workgroup per pair of Q tiles, no chaining) it gains 1-3 % at d = 128 from N = 2048 on.
-    const bool causal = mask == FA2_MASK_CAUSAL;
-    const long long qt256 = Nq / kRows256;
-    const long long wg256 = (long long)B * H * (causal ? (qt256 + 1) / 2 : qt256);
-    const bool whole_rounds = wg256 % kCUs == 0;   // unmasked: then one workgroup per CU chains a Q tile of every round
-    const bool rows256 = d <= 128 && Nq == Nk && Nq % kRows256 == 0 &&
-                         (causal ? d == 128 && Nq >= 2048 && (whole_rounds || wg256 >= 16 * kCUs)
-                                 : (whole_rounds && (d == 128 || Nq >= 2048)) ||
-                                       (d == 128 && wg256 >= 16 * kCUs && Nq >= 2048));
-    variant = rows256 ? FA2_VARIANT_NARROW8 : FA2_VARIANT_NARROW;
-  }
+  if (variant == FA2_VARIANT_AUTO) variant = choose_variant(B, H, Nq, Nk, d, mask);
   if (variant != FA2_VARIANT_NARROW) {
     // the 256-row shape: whole tiles, square, d <= 128
     if (Nq != Nk || Nq % kRows256 != 0 || d == 256) return FA2_ERR_UNSUPPORTED;
@@ -910,6 +913,14 @@ extern "C" int fa2_fwd_qk(const void* Q, const void* K, const void* V, void* O, 
 extern "C" int fa2_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H, int N, int d,
                        float scale, int dtype, void* stream) {
   return run(Q, K, V, O, LSE, B, H, N, N, d, scale, dtype, FA2_VARIANT_AUTO, FA2_MASK_NONE, stream);
+}
+
+extern "C" int fa2_tile_shape(int B, int H, int Nq, int Nk, int d, int mask) {
+  if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0) return FA2_ERR_INVALID_ARG;
+  if (mask != FA2_MASK_NONE && mask != FA2_MASK_CAUSAL) return FA2_ERR_INVALID_ARG;
+  if (d != 64 && d != 128 && d != 256) return FA2_ERR_UNSUPPORTED;
+  if (mask == FA2_MASK_CAUSAL && Nq != Nk) return FA2_ERR_UNSUPPORTED;
+  return choose_variant(B, H, Nq, Nk, d, mask);
 }
 
 extern "C" const char* fa2_strerror(int code) {

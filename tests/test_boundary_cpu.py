@@ -18,7 +18,8 @@ def _declared_functions():
 
 
 def test_header_declares_the_boundary():
-    assert {"fa2_fwd", "fa2_fwd_variant", "fa2_fwd_masked", "fa2_fwd_qk", "fa2_strerror", "fa2_version"} <= set(_declared_functions())
+    assert {"fa2_fwd", "fa2_fwd_variant", "fa2_fwd_masked", "fa2_fwd_qk", "fa2_tile_shape", "fa2_strerror",
+            "fa2_version"} <= set(_declared_functions())
 
 
 def test_library_exports_every_declared_symbol():
@@ -143,3 +144,38 @@ def test_torch_wrapper_refuses_cpu_tensors():
     x = torch.zeros(1, 128, 1, 64, dtype=torch.float16)
     with pytest.raises(ValueError):
         fa2.fa2_fwd(x, x, x, 0.125)
+
+
+def test_tile_shape_choice_follows_the_documented_rule():
+    # host logic only: which tile shape the entry points without a `variant` argument take (no launch, no GPU)
+    from paper_2312_11918_amd import workloads
+    N8, N4 = fa2.FA2_VARIANT_NARROW8, fa2.FA2_VARIANT_NARROW
+    expect = {1: N4, 2: N4, 3: N8, 4: N8, 5: N8}   # the five workloads: tiny and N = 512 at d = 64 stay in 128 rows
+    for i, w in workloads.CONFIGS.items():
+        assert fa2.fa2_tile_shape(w.B, w.H, w.N, w.N, w.d) == expect[i], w.name
+    # the paper's shapes
+    assert fa2.fa2_tile_shape(4, 32, 4096, 4096, 64) == N8
+    assert fa2.fa2_tile_shape(4, 16, 4096, 4096, 128) == N8
+    assert fa2.fa2_tile_shape(4, 8, 4096, 4096, 256) == N4          # d = 256 exists in the 128-row shape only
+    # whole rounds of the 256 CUs decide: 3 x 16 heads x 8 tiles = 384 tiles is one and a half rounds
+    assert fa2.fa2_tile_shape(3, 16, 2048, 2048, 128) == N4
+    assert fa2.fa2_tile_shape(4, 16, 2048, 2048, 128) == N8
+    # ... unless the tiles are very many (d = 128, N >= 2048)
+    assert fa2.fa2_tile_shape(33, 16, 4096, 4096, 128) == N8         # 8448 tiles, 33 rounds
+    assert fa2.fa2_tile_shape(33, 16, 1024, 1024, 128) == N4
+    # partial tiles, Nq != Nk
+    assert fa2.fa2_tile_shape(8, 16, 2047, 2047, 128) == N4
+    assert fa2.fa2_tile_shape(8, 16, 2048, 4096, 128) == N4
+    # d = 64: only from N = 2048 on
+    assert fa2.fa2_tile_shape(16, 32, 1024, 1024, 64) == N4
+    assert fa2.fa2_tile_shape(8, 32, 2048, 2048, 64) == N8
+    # causal: d = 128 from N = 2048 on (pairs of Q tiles fill the rounds), never at d = 64
+    C = fa2.FA2_MASK_CAUSAL
+    assert fa2.fa2_tile_shape(8, 16, 2048, 2048, 128, C) == N8
+    assert fa2.fa2_tile_shape(16, 16, 1024, 1024, 128, C) == N4
+    assert fa2.fa2_tile_shape(1, 32, 16384, 16384, 64, C) == N4
+    # refused like the launching entry points refuse
+    assert fa2.fa2_tile_shape(1, 1, 128, 128, 96) == fa2.FA2_ERR_UNSUPPORTED
+    assert fa2.fa2_tile_shape(1, 1, 128, 256, 64, C) == fa2.FA2_ERR_UNSUPPORTED
+    assert fa2.fa2_tile_shape(0, 1, 128, 128, 64) == fa2.FA2_ERR_INVALID_ARG
+    assert fa2.fa2_tile_shape(1, 1, 128, 128, 64, 7) == fa2.FA2_ERR_INVALID_ARG
